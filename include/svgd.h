@@ -1,0 +1,107 @@
+/*
+ * svgd.h - C ABI of the MI355X (gfx950) SVGD all-particle update library.
+ *
+ * One SVGD step over n particles (paper App. B.2, "SVGD in Push": the leader's per-pair kernel
+ * and kernel-gradient accumulation followed by the followers' in-place parameter update), in the
+ * score/ascent convention and with the median-heuristic bandwidth:
+ *
+ *     d2_ij  = |x_i - x_j|^2
+ *     h      = median(all n*n entries of d2) / ln(n+1)        (h <= 0 -> h = 1)
+ *     K_ij   = exp(-d2_ij / h)                                 (the paper's exp(-|.|^2/(2 l^2)), h = 2 l^2)
+ *     phi_i  = (1/n) sum_j [ K_ij g_j + (2/h) K_ij (x_i - x_j) ]
+ *     x_i   <- x_i + eps * phi_i                               (every phi_i from the pre-step X)
+ *
+ * Particle i is the flattened parameter vector of one network (App. B.2: flatten(params)); g_i is
+ * its score grad log p(x_i) (a caller holding loss gradients passes g = -grad; parameters
+ * without a gradient contribute zeros, as in the paper's routine).
+ *
+ * Conventions for every entry point
+ *   - X, G, PHI are DEVICE pointers to n x D fp32, row-major, leading dimension D (row i starts
+ *     at element i*D).  Only 4-byte alignment is required.  D is 64-bit.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; calls return before the work completes unless stated otherwise.
+ *   - The caller owns X, G, PHI.  The handle owns its scratch (partial sums, K, h), allocated
+ *     once in svgd_create and freed in svgd_destroy; svgd_step/svgd_phi/svgd_bandwidth never
+ *     allocate.  One handle must not be used from two streams at once.
+ *   - Return value: SVGD_OK (0) or a negative svgd_status.  No entry point aborts or throws.
+ *     Non-finite DATA is not checked and propagates as IEEE NaN/Inf.
+ */
+#ifndef SVGD_H
+#define SVGD_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct svgd_ctx *svgd_handle_t;
+
+enum svgd_status {
+    SVGD_OK = 0,
+    SVGD_ERR_INVALID_ARG = -1, /* null pointer, n < 1, D < 1, non-finite eps, X aliases G/PHI */
+    SVGD_ERR_BAD_HANDLE = -2,  /* null handle or handle already destroyed */
+    SVGD_ERR_TOO_LARGE = -3,   /* n > max_n, D > max_D, or max_n beyond SVGD_MAX_PARTICLES */
+    SVGD_ERR_ALLOC = -4,       /* device or host allocation failed */
+    SVGD_ERR_DEVICE = -5       /* a HIP call failed; see svgd_last_device_error */
+};
+
+#define SVGD_MAX_PARTICLES 64
+
+/*
+ * Create a handle for problems up to max_n particles (1..SVGD_MAX_PARTICLES) of up to max_D
+ * parameters each on HIP device `device_id` (-1 = the current device).  `flags` must be 0.
+ * Allocates the handle's device scratch (about 20 MB).  On success *out receives the handle.
+ */
+int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uint32_t flags);
+
+/*
+ * Fix the bandwidth: h > 0 selects the paper's fixed-lengthscale kernel (App. B.2,
+ * `lengthscale` l with h = 2 l^2) and skips the median; h <= 0 restores the median heuristic
+ * (the default).  Takes effect for subsequent calls.
+ */
+int svgd_set_bandwidth(svgd_handle_t h, double h_fixed);
+
+/*
+ * Compute d2, h, K and the row sums of K for X (device, n x D) and keep them in the handle
+ * (App. B.2: the radius^2 / exp step of the per-pair kernel, done once for all pairs).
+ * If h_out_host is non-NULL the stream is synchronised and *h_out_host (HOST memory) receives h;
+ * with NULL nothing is copied and the call does not synchronise.
+ */
+int svgd_bandwidth(svgd_handle_t h, const float *X, int n, int64_t D, double *h_out_host,
+                   void *stream);
+
+/*
+ * One whole SVGD step, in place: X <- X + eps * phi(X, G).  X (device, n x D) is read, then
+ * overwritten; G (device, n x D) is read only (App. B.2: kernel, kernel-gradient accumulation and
+ * the followers' `p.add_` update, all particles at once).  Does not synchronise or allocate.
+ */
+int svgd_step(svgd_handle_t h, float *X, const float *G, int n, int64_t D, float eps, void *stream);
+
+/*
+ * Diagnostic variant of svgd_step: the same kernels, but phi itself is written to PHI
+ * (device, n x D) and X is left untouched.
+ */
+int svgd_phi(svgd_handle_t h, const float *X, const float *G, int n, int64_t D, float *PHI,
+             void *stream);
+
+/*
+ * Copy the bandwidth and kernel matrix of the most recent svgd_bandwidth/svgd_step/svgd_phi call
+ * to HOST memory: *h_out (nullable) receives h; K_host (nullable, n*n floats, row-major)
+ * receives K.  Synchronises `stream` first.  INVALID_ARG if no step has run yet.
+ */
+int svgd_get_last(svgd_handle_t h, double *h_out, float *K_host, void *stream);
+
+/* Free the handle's scratch and invalidate the handle.  The caller synchronises beforehand. */
+int svgd_destroy(svgd_handle_t h);
+
+/* hipError_t value of the most recent failed HIP call on this handle (0 if none). */
+int svgd_last_device_error(svgd_handle_t h);
+
+/* Static, human-readable name of a status code. */
+const char *svgd_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVGD_H */

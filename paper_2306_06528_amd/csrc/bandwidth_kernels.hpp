@@ -1,0 +1,123 @@
+// Pass 2: from the reduced pair sums to d2, the median-heuristic bandwidth h, the RBF kernel
+// matrix K, its row sums, and the coefficient tables of the update kernels.  One workgroup,
+// fp64 throughout (at most 2016 pairs: the cost is nil and none of the 1e-5 budget on h and K
+// is spent here).  Nothing returns to the host: the paper's routine (App. B.2) reads each kernel
+// value back with `.item()`; here K stays on the device.
+#pragma once
+#include "common.hpp"
+
+namespace svgd {
+
+constexpr int kBwThreads = 1024;
+
+__device__ inline int pair_index(int i, int j, int n) { return i * n - (i * (i + 1)) / 2 + (j - i - 1); } // i < j
+
+__global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__restrict__ part2,
+                                                               int nslices, int n, int mode,
+                                                               double h_fixed,
+                                                               DevState *__restrict__ st,
+                                                               float *__restrict__ coef)
+{
+    __shared__ double S[kMaxPairsFull];              // reduced sums, later K per pair
+    __shared__ double pr[kMaxN * (kMaxN - 1) / 2];   // d2 per unordered pair i < j
+    __shared__ double sel[2];
+    __shared__ double h_sh;
+
+    const int tid = threadIdx.x;
+    const int P = n * (n + 1) / 2;
+    const int Pp = n * (n - 1) / 2;
+
+    for (int p = tid; p < P; p += kBwThreads) {
+        double s = 0.0;
+        for (int k = 0; k < nslices; ++k) s += part2[(int64_t)k * P + p];
+        S[p] = s;
+    }
+    if (tid < 2) sel[tid] = 0.0;
+    __syncthreads();
+
+    // d2 per pair: direct sums, or S_ii + S_jj - 2 S_ij (clamped at 0) from the centred Gram
+    for (int e = tid; e < n * n; e += kBwThreads) {
+        const int i = e / n, j = e % n;
+        if (i < j) {
+            double d;
+            if (mode == kModeDiff) {
+                d = S[tri(i, j, n)];
+            } else {
+                d = S[tri(i, i, n)] + S[tri(j, j, n)] - 2.0 * S[tri(i, j, n)];
+                if (d < 0.0) d = 0.0;
+            }
+            pr[pair_index(i, j, n)] = d;
+        }
+    }
+    __syncthreads();
+
+    // Median of the multiset of all n*n entries of d2: n diagonal zeros plus every pair value
+    // twice.  Sorted position t of the full list is 0 for t < n and the ((t-n)/2)-th smallest
+    // pair value otherwise; an even count averages positions n*n/2 - 1 and n*n/2.  The two
+    // order statistics are found by rank counting (ties broken by index).
+    if (h_fixed <= 0.0 && Pp > 0) {
+        const int n2 = n * n;
+        const int t_lo = (n2 - 1) / 2, t_hi = n2 / 2;
+        const int k_lo = (t_lo >= n) ? (t_lo - n) / 2 : -1;
+        const int k_hi = (t_hi >= n) ? (t_hi - n) / 2 : -1;
+        for (int e = tid; e < Pp; e += kBwThreads) {
+            const double v = pr[e];
+            int rank = 0;
+            for (int f = 0; f < Pp; ++f) {
+                const double w = pr[f];
+                rank += (w < v || (w == v && f < e)) ? 1 : 0;
+            }
+            if (rank == k_lo) sel[0] = v;
+            if (rank == k_hi) sel[1] = v;
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double med = 0.5 * (sel[0] + sel[1]);
+        double h = (h_fixed > 0.0) ? h_fixed : med / log((double)n + 1.0);
+        if (!(h > 0.0)) h = 1.0;
+        h_sh = h;
+        st->h = h;
+        st->med = med;
+        // a single particle has no repulsive term at all: make that exact (phi = g)
+        st->two_over_h = (n == 1) ? 0.f : (float)(2.0 / h);
+        st->n = n;
+    }
+    __syncthreads();
+    const double h = h_sh;
+    const double c2h = (n == 1) ? 0.0 : 2.0 / h;
+
+    for (int e = tid; e < Pp; e += kBwThreads) S[e] = exp(-pr[e] / h); // K per pair, reusing S
+    __syncthreads();
+    if (tid < n) {
+        double r = 1.0;
+        for (int j = 0; j < n; ++j)
+            if (j != tid) r += S[tid < j ? pair_index(tid, j, n) : pair_index(j, tid, n)];
+        coef[kOffRho + tid] = (float)(c2h * r / (double)n);
+    }
+    for (int e = tid; e < n * n; e += kBwThreads) {
+        const int i = e / n, j = e % n;
+        const double k = (i == j) ? 1.0 : S[i < j ? pair_index(i, j, n) : pair_index(j, i, n)];
+        coef[kOffK + e] = (float)k;
+        coef[kOffC + e] = (float)(k / (double)n);
+    }
+    // A operands of v_mfma_f32_16x16x4_f32 for the matrix-core update kernel: for output block
+    // bi and step s = 4b + r, lane (q = lane/16, m = lane%16) holds C[16bi + m][16b + 4q + r].
+    if (n > 16) {
+        const int NB = (n + 15) / 16;
+        const int total = NB * 4 * NB * kWave;
+        for (int e = tid; e < total; e += kBwThreads) {
+            const int lane = e & 63;
+            const int s = (e >> 6) % (4 * NB);
+            const int bi = (e >> 6) / (4 * NB);
+            const int i = 16 * bi + (lane & 15);
+            const int j = 16 * (s >> 2) + 4 * (lane >> 4) + (s & 3);
+            double c = 0.0;
+            if (i < n && j < n)
+                c = ((i == j) ? 1.0 : S[i < j ? pair_index(i, j, n) : pair_index(j, i, n)]) / (double)n;
+            coef[kOffAT + e] = (float)c;
+        }
+    }
+}
+
+} // namespace svgd

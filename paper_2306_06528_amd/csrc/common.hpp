@@ -1,0 +1,73 @@
+// Shared device-side helpers and the layout of the handle's device state.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace svgd {
+
+constexpr int kMaxN = 64;                              // particles
+constexpr int kMaxPairsFull = kMaxN * (kMaxN + 1) / 2; // upper triangle with diagonal
+constexpr int kWave = 64;
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+// rows of X start at i*D floats, so a 4-column group is only 4-byte aligned in general
+typedef float f32x4u __attribute__((ext_vector_type(4), aligned(4)));
+
+// Partial-sum formats written by the Gram kernels, both indexed by tri(i, j), i <= j.
+enum GramMode : int {
+    kModeDiff = 0, // entry (i<j) holds sum_k (x_ik - x_jk)^2; diagonal entries are 0
+    kModeGram = 1  // entry (i<=j) holds sum_k y_ik y_jk of the column-centred y = x - mean_i x
+};
+
+__host__ __device__ inline int tri(int i, int j, int n) { return i * n - (i * (i - 1)) / 2 + (j - i); }
+
+// Everything the update kernels need from the bandwidth kernel, in device memory.
+struct DevState {
+    double h;
+    double med;
+    float two_over_h;
+    int n;
+};
+
+// Offsets (in floats) into the handle's coefficient block.
+//   C   [n*n]   C_ij = K_ij / n
+//   RHO [n]     rho_i = (2/h) * (sum_j K_ij) / n
+//   K   [n*n]   K_ij (kept for svgd_get_last)
+//   AT  [..]    C re-ordered into per-lane MFMA A operands for the matrix-core update kernel
+constexpr int kOffC = 0;
+constexpr int kOffRho = kOffC + kMaxN * kMaxN;
+constexpr int kOffK = kOffRho + kMaxN;
+constexpr int kOffAT = kOffK + kMaxN * kMaxN;
+constexpr int kCoefFloats = kOffAT + (kMaxN / 16) * (kMaxN / 4) * kWave;
+
+__device__ inline f32x4 load4(const float *__restrict__ row, int64_t col, int64_t D, bool full)
+{
+    if (full) return *reinterpret_cast<const f32x4u *>(row + col);
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (col + 0 < D) v.x = row[col + 0];
+    if (col + 1 < D) v.y = row[col + 1];
+    if (col + 2 < D) v.z = row[col + 2];
+    if (col + 3 < D) v.w = row[col + 3];
+    return v;
+}
+
+__device__ inline void store4(float *__restrict__ row, int64_t col, int64_t D, bool full, f32x4 v)
+{
+    if (full) {
+        *reinterpret_cast<f32x4u *>(row + col) = v;
+        return;
+    }
+    if (col + 0 < D) row[col + 0] = v.x;
+    if (col + 1 < D) row[col + 1] = v.y;
+    if (col + 2 < D) row[col + 2] = v.z;
+    if (col + 3 < D) row[col + 3] = v.w;
+}
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
+    return v;
+}
+
+} // namespace svgd

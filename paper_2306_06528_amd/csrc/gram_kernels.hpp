@@ -1,0 +1,215 @@
+// Pairwise squared distances, pass 1: per-workgroup partial sums over a split of the D columns.
+//
+// Paper App. B.2 computes, per ordered pair, diff = (p_j - p_i)/l and radius^2 = dot(diff, diff).
+// Here all pairs are accumulated in ONE pass over X: a thread (or a wave) holds all n values of
+// a few columns on chip, adds their contribution to every pair, and moves on.
+#pragma once
+#include "common.hpp"
+
+namespace svgd {
+
+// ---------------------------------------------------------------------------------------------
+// n <= 16: vector ALU, lanes = columns.  Each thread loads 4 consecutive columns of every row
+// (one 16-byte load per row, 1 KiB contiguous per row per wave) and keeps one fp32 accumulator
+// per pair in registers.
+//   N <= 8 : direct differences (x_i - x_j)^2 - no cancellation at all.
+//   N  > 8 : Gram of the column-centred y = x - mean_i(x); d2 = S_ii + S_jj - 2 S_ij later.
+// Chains are short (D / (4 * threads) terms per accumulator); lanes are combined by shuffles,
+// waves through LDS, workgroups in fp64 by the reduce kernel.
+// ---------------------------------------------------------------------------------------------
+template <int N>
+__global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict__ X, int64_t D,
+                                                        float *__restrict__ partials)
+{
+    constexpr bool kDiff = (N <= 8);
+    constexpr int P = N * (N + 1) / 2;
+    float acc[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) acc[p] = 0.f;
+
+    const int64_t ngroups = (D + 3) >> 2;
+    const int64_t nthreads = (int64_t)gridDim.x * 256;
+    for (int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x; grp < ngroups; grp += nthreads) {
+        const int64_t col = grp << 2;
+        const bool full = (col + 4 <= D);
+        f32x4 x[N];
+#pragma unroll
+        for (int j = 0; j < N; ++j) x[j] = load4(X + (int64_t)j * D, col, D, full);
+        if constexpr (kDiff) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+#pragma unroll
+                for (int j = i + 1; j < N; ++j) {
+                    const f32x4 d = x[i] - x[j];
+                    float a = acc[tri(i, j, N)];
+                    a = fmaf(d.x, d.x, a);
+                    a = fmaf(d.y, d.y, a);
+                    a = fmaf(d.z, d.z, a);
+                    a = fmaf(d.w, d.w, a);
+                    acc[tri(i, j, N)] = a;
+                }
+            }
+        } else {
+            f32x4 m = x[0];
+#pragma unroll
+            for (int j = 1; j < N; ++j) m += x[j];
+            m *= (1.0f / N);
+#pragma unroll
+            for (int j = 0; j < N; ++j) x[j] -= m; // columns beyond D were loaded as 0 -> stay 0
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+#pragma unroll
+                for (int j = i; j < N; ++j) {
+                    float a = acc[tri(i, j, N)];
+                    a = fmaf(x[i].x, x[j].x, a);
+                    a = fmaf(x[i].y, x[j].y, a);
+                    a = fmaf(x[i].z, x[j].z, a);
+                    a = fmaf(x[i].w, x[j].w, a);
+                    acc[tri(i, j, N)] = a;
+                }
+            }
+        }
+    }
+
+    __shared__ float red[4][P];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        const float v = wave_sum(acc[p]);
+        if (lane == 0) red[wave][p] = v;
+    }
+    __syncthreads();
+    for (int p = threadIdx.x; p < P; p += 256)
+        partials[(int64_t)blockIdx.x * P + p] = (red[0][p] + red[1][p]) + (red[2][p] + red[3][p]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// 16 < n <= 64: matrix cores.  The Gram S = Y Y^T of the column-centred Y is a contraction over
+// columns, so the MFMA A and B operands are both "lane = (particle row, column slot)".  Loading
+// that shape straight from HBM would touch 16 rows per quarter-wave, so each wave instead
+//   1. loads a 16*NB-row x 64-column slab with row-contiguous 16-byte loads (256 B per row per
+//      quarter-wave), rows {4i + lane/16}, columns 4*(lane%16)..+3,
+//   2. centres the columns (own rows in registers, two cross-lane adds for the other rows),
+//   3. writes the slab to a wave-private LDS region with a 16-byte-granule XOR swizzle,
+//   4. reads it back as v_mfma_f32_16x16x4_f32 operands: lane (q = lane/16, rr = lane%16) takes
+//      row 16b+rr, 4 columns per read; the 4 k-slots of one MFMA are columns {16s+4q+c, q=0..3},
+//   5. issues one MFMA per unordered block pair (b <= b'), fp32 accumulators in registers:
+//      lane (q, c), register r of pair (b, b') holds S[16b + 4q + r][16b' + c].
+// Any assignment of columns to k-slots is valid because every column is summed exactly once.
+// ---------------------------------------------------------------------------------------------
+template <int NB>
+__global__ __launch_bounds__(128) void gram_mfma_kernel(const float *__restrict__ X, int n,
+                                                        int64_t D, float *__restrict__ partials)
+{
+    constexpr int ROWS = 16 * NB;
+    constexpr int RPL = 4 * NB; // rows per lane while loading
+    constexpr int NPAIR = NB * (NB + 1) / 2;
+    __shared__ float lds[2][ROWS * 64];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = lane >> 4, c16 = lane & 15;
+    float *my = lds[wave];
+    const float inv_n = 1.0f / (float)n;
+
+    f32x4 acc[NPAIR];
+#pragma unroll
+    for (int p = 0; p < NPAIR; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const int64_t ntile = (D + 127) >> 7;
+    for (int64_t tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+        const int64_t wcol = (tile << 7) + (wave << 6);
+        const int64_t col = wcol + 4 * c16;
+        const bool full = (wcol + 64 <= D);
+        f32x4 x[RPL];
+#pragma unroll
+        for (int i = 0; i < RPL; ++i) {
+            const int row = 4 * i + q;
+            x[i] = (row < n) ? load4(X + (int64_t)row * D, col, D, full) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+        f32x4 s = x[0];
+#pragma unroll
+        for (int i = 1; i < RPL; ++i) s += x[i];
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            float v = s[c];
+            v += __shfl_xor(v, 16, kWave);
+            v += __shfl_xor(v, 32, kWave);
+            s[c] = v * inv_n;
+        }
+        __syncthreads(); // the previous slab has been consumed
+#pragma unroll
+        for (int i = 0; i < RPL; ++i) {
+            const int row = 4 * i + q;
+            // rows >= n hold -mean here; they only reach entries with i or j >= n, never stored
+            *reinterpret_cast<f32x4 *>(&my[row * 64 + ((c16 ^ (row & 15)) << 2)]) = x[i] - s;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int st = 0; st < 4; ++st) {
+            f32x4 a[NB];
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int row = 16 * b + c16; // here c16 plays the role of rr (matrix row)
+                a[b] = *reinterpret_cast<const f32x4 *>(&my[row * 64 + (((4 * st + q) ^ c16) << 2)]);
+            }
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                int p = 0;
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+#pragma unroll
+                    for (int b2 = b; b2 < NB; ++b2) {
+                        acc[p] = __builtin_amdgcn_mfma_f32_16x16x4f32(a[b][c], a[b2][c], acc[p], 0, 0, 0);
+                        ++p;
+                    }
+                }
+            }
+        }
+    }
+
+    // combine the two waves through LDS, then store the upper triangle in tri(i, j) order
+    __syncthreads();
+    float *xch = &lds[0][0];
+    if (wave == 1) {
+#pragma unroll
+        for (int p = 0; p < NPAIR; ++p)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) xch[(p * 4 + r) * 64 + lane] = acc[p][r];
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const int P = n * (n + 1) / 2;
+        float *out = partials + (int64_t)blockIdx.x * P;
+        int p = 0;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int b2 = b; b2 < NB; ++b2) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int i = 16 * b + 4 * q + r;
+                    const int j = 16 * b2 + c16;
+                    const float v = acc[p][r] + xch[(p * 4 + r) * 64 + lane];
+                    if (i <= j && j < n) out[tri(i, j, n)] = v;
+                }
+                ++p;
+            }
+        }
+    }
+}
+
+// Sum the per-workgroup fp32 partials in fp64, split into `nslices` interleaved slices so that
+// many threads share the work: part2[slice][p] = sum_{k = slice (mod nslices)} partials[k][p].
+__global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partials,
+                                                              int nparts, int P, int nslices,
+                                                              double *__restrict__ part2)
+{
+    const int p = blockIdx.x * 256 + threadIdx.x;
+    const int slice = blockIdx.y;
+    if (p >= P) return;
+    double s = 0.0;
+    for (int k = slice; k < nparts; k += nslices) s += (double)partials[(int64_t)k * P + p];
+    part2[(int64_t)slice * P + p] = s;
+}
+
+} // namespace svgd

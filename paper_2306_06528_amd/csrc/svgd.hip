@@ -1,0 +1,371 @@
+// Host side of the C ABI declared in include/svgd.h: handle, argument validation, launches.
+#include "../../include/svgd.h"
+
+#include <cmath>
+#include <cstdlib>
+#include <mutex>
+#include <new>
+#include <unordered_set>
+
+#include "bandwidth_kernels.hpp"
+#include "common.hpp"
+#include "gram_kernels.hpp"
+#include "update_kernels.hpp"
+
+using namespace svgd;
+
+namespace {
+
+constexpr uint32_t kMagic = 0x53564744u; // "SVGD"
+constexpr int kMaxParts = 2048;          // upper bound on Gram workgroups (= partial vectors)
+constexpr int kMaxSlices = 32;
+
+} // namespace
+
+struct svgd_ctx {
+    uint32_t magic;
+    int device;
+    int max_n;
+    int64_t max_D;
+    int num_cu;
+    double h_fixed;
+    int last_n; // 0 = nothing computed yet
+    int last_hip_error;
+    float *partials;  // [kMaxParts][P]
+    double *part2;    // [kMaxSlices][P]
+    DevState *state;
+    float *coef;      // kCoefFloats
+};
+
+namespace {
+
+struct DeviceGuard {
+    int prev = -1;
+    bool switched = false;
+    explicit DeviceGuard(int dev)
+    {
+        if (hipGetDevice(&prev) == hipSuccess && prev != dev) switched = (hipSetDevice(dev) == hipSuccess);
+    }
+    ~DeviceGuard()
+    {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+int fail(svgd_ctx *c, hipError_t e)
+{
+    if (c) c->last_hip_error = (int)e;
+    return SVGD_ERR_DEVICE;
+}
+
+// Live handles are kept in a registry so that a stale pointer (use after destroy) is rejected
+// without being dereferenced.
+std::mutex g_live_mutex;
+std::unordered_set<svgd_ctx *> &live_handles()
+{
+    static std::unordered_set<svgd_ctx *> s;
+    return s;
+}
+
+int check_handle(svgd_ctx *c)
+{
+    if (!c) return SVGD_ERR_BAD_HANDLE;
+    std::lock_guard<std::mutex> lock(g_live_mutex);
+    if (!live_handles().count(c) || c->magic != kMagic) return SVGD_ERR_BAD_HANDLE;
+    return SVGD_OK;
+}
+
+int check_shape(svgd_ctx *c, int n, int64_t D)
+{
+    if (n < 1 || D < 1) return SVGD_ERR_INVALID_ARG;
+    if (n > c->max_n || D > c->max_D) return SVGD_ERR_TOO_LARGE;
+    return SVGD_OK;
+}
+
+bool overlaps(const float *a, const float *b, int n, int64_t D)
+{
+    const uintptr_t bytes = (uintptr_t)n * (uintptr_t)D * sizeof(float);
+    const uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
+    return pa < pb + bytes && pb < pa + bytes;
+}
+
+template <int N>
+void launch_gram_valu(const float *X, int64_t D, float *partials, int grid, hipStream_t s)
+{
+    gram_valu_kernel<N><<<grid, 256, 0, s>>>(X, D, partials);
+}
+
+template <int N, bool EMIT>
+void launch_update_valu(float *X, const float *G, float *PHI, const float *coef, const DevState *st,
+                        int64_t D, float eps, int grid, hipStream_t s)
+{
+    update_valu_kernel<N, EMIT><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, eps);
+}
+
+#define SVGD_SWITCH_N(n, CALL)                                                                     \
+    switch (n) {                                                                                   \
+    case 1: CALL(1); break;                                                                        \
+    case 2: CALL(2); break;                                                                        \
+    case 3: CALL(3); break;                                                                        \
+    case 4: CALL(4); break;                                                                        \
+    case 5: CALL(5); break;                                                                        \
+    case 6: CALL(6); break;                                                                        \
+    case 7: CALL(7); break;                                                                        \
+    case 8: CALL(8); break;                                                                        \
+    case 9: CALL(9); break;                                                                        \
+    case 10: CALL(10); break;                                                                      \
+    case 11: CALL(11); break;                                                                      \
+    case 12: CALL(12); break;                                                                      \
+    case 13: CALL(13); break;                                                                      \
+    case 14: CALL(14); break;                                                                      \
+    case 15: CALL(15); break;                                                                      \
+    default: CALL(16); break;                                                                      \
+    }
+
+int clampi(int64_t v, int lo, int hi) { return (int)(v < lo ? lo : (v > hi ? hi : v)); }
+
+// Passes 1 and 2: Gram partials -> fp64 reduction -> h, K, coefficient tables (all on `s`).
+int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t s)
+{
+    const int P = n * (n + 1) / 2;
+    int nparts, mode;
+    if (n <= 16) {
+        const int64_t ngroups = (D + 3) / 4;
+        nparts = clampi((ngroups + 255) / 256, 1, c->num_cu * 4);
+        mode = (n <= 8) ? kModeDiff : kModeGram;
+#define CALL(N) launch_gram_valu<N>(X, D, c->partials, nparts, s)
+        SVGD_SWITCH_N(n, CALL)
+#undef CALL
+    } else {
+        const int64_t ntile = (D + 127) / 128;
+        nparts = clampi(ntile, 1, c->num_cu * 4);
+        mode = kModeGram;
+        const int NB = (n + 15) / 16;
+        if (NB == 2)
+            gram_mfma_kernel<2><<<nparts, 128, 0, s>>>(X, n, D, c->partials);
+        else if (NB == 3)
+            gram_mfma_kernel<3><<<nparts, 128, 0, s>>>(X, n, D, c->partials);
+        else
+            gram_mfma_kernel<4><<<nparts, 128, 0, s>>>(X, n, D, c->partials);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, e);
+
+    const int nslices = nparts < kMaxSlices ? nparts : kMaxSlices;
+    reduce_partials_kernel<<<dim3((P + 255) / 256, nslices), 256, 0, s>>>(c->partials, nparts, P,
+                                                                         nslices, c->part2);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, e);
+    bandwidth_kernel<<<1, kBwThreads, 0, s>>>(c->part2, nslices, n, mode, c->h_fixed, c->state, c->coef);
+    e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, e);
+    c->last_n = n;
+    return SVGD_OK;
+}
+
+// Pass 3.  EMIT = false: X updated in place; EMIT = true: phi written to PHI.
+template <bool EMIT>
+int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, float eps,
+               hipStream_t s)
+{
+    if (n <= 16) {
+        const int64_t ngroups = (D + 3) / 4;
+        const int grid = clampi((ngroups + 255) / 256, 1, c->num_cu * 8);
+#define CALL(N) launch_update_valu<N, EMIT>(X, G, PHI, c->coef, c->state, D, eps, grid, s)
+        SVGD_SWITCH_N(n, CALL)
+#undef CALL
+    } else {
+        const int64_t ntile = (D + 63) / 64;
+        const int grid = clampi((ntile + 3) / 4, 1, c->num_cu * 2);
+        const int NB = (n + 15) / 16;
+        if (NB == 2)
+            update_mfma_kernel<2, EMIT><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps);
+        else if (NB == 3)
+            update_mfma_kernel<3, EMIT><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps);
+        else
+            update_mfma_kernel<4, EMIT><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps);
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, e);
+    return SVGD_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uint32_t flags)
+{
+    if (!out) return SVGD_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (max_n < 1 || max_D < 1 || flags != 0 || device_id < -1) return SVGD_ERR_INVALID_ARG;
+    if (max_n > SVGD_MAX_PARTICLES) return SVGD_ERR_TOO_LARGE;
+
+    svgd_ctx *c = new (std::nothrow) svgd_ctx();
+    if (!c) return SVGD_ERR_ALLOC;
+    c->magic = 0;
+    c->max_n = max_n;
+    c->max_D = max_D;
+    c->h_fixed = 0.0;
+    c->last_n = 0;
+    c->last_hip_error = 0;
+    c->partials = nullptr;
+    c->part2 = nullptr;
+    c->state = nullptr;
+    c->coef = nullptr;
+
+    hipError_t e;
+    int dev = device_id;
+    if (dev < 0) {
+        e = hipGetDevice(&dev);
+        if (e != hipSuccess) { delete c; return SVGD_ERR_DEVICE; }
+    }
+    int count = 0;
+    e = hipGetDeviceCount(&count);
+    if (e != hipSuccess || dev >= count) { delete c; return e != hipSuccess ? SVGD_ERR_DEVICE : SVGD_ERR_INVALID_ARG; }
+    c->device = dev;
+    DeviceGuard guard(dev);
+    int cus = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess || cus < 1) { delete c; return SVGD_ERR_DEVICE; }
+    c->num_cu = cus > 512 ? 512 : cus; // keeps every persistent grid within kMaxParts workgroups
+
+    const size_t P = (size_t)max_n * (max_n + 1) / 2;
+    bool ok = hipMalloc(&c->partials, (size_t)kMaxParts * P * sizeof(float)) == hipSuccess &&
+              hipMalloc(&c->part2, (size_t)kMaxSlices * P * sizeof(double)) == hipSuccess &&
+              hipMalloc(&c->state, sizeof(DevState)) == hipSuccess &&
+              hipMalloc(&c->coef, (size_t)kCoefFloats * sizeof(float)) == hipSuccess;
+    if (!ok) {
+        (void)hipGetLastError();
+        (void)hipFree(c->partials);
+        (void)hipFree(c->part2);
+        (void)hipFree(c->state);
+        (void)hipFree(c->coef);
+        delete c;
+        return SVGD_ERR_ALLOC;
+    }
+    c->magic = kMagic;
+    {
+        std::lock_guard<std::mutex> lock(g_live_mutex);
+        live_handles().insert(c);
+    }
+    *out = c;
+    return SVGD_OK;
+}
+
+int svgd_set_bandwidth(svgd_handle_t c, double h_fixed)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    if (std::isnan(h_fixed) || std::isinf(h_fixed)) return SVGD_ERR_INVALID_ARG;
+    c->h_fixed = h_fixed > 0.0 ? h_fixed : 0.0;
+    return SVGD_OK;
+}
+
+int svgd_bandwidth(svgd_handle_t c, const float *X, int n, int64_t D, double *h_out_host, void *stream)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    if (!X) return SVGD_ERR_INVALID_ARG;
+    rc = check_shape(c, n, D);
+    if (rc) return rc;
+    DeviceGuard guard(c->device);
+    hipStream_t s = (hipStream_t)stream;
+    rc = run_kernel_matrix(c, X, n, D, s);
+    if (rc) return rc;
+    if (h_out_host) {
+        hipError_t e = hipMemcpyAsync(h_out_host, &c->state->h, sizeof(double), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) return fail(c, e);
+    }
+    return SVGD_OK;
+}
+
+int svgd_step(svgd_handle_t c, float *X, const float *G, int n, int64_t D, float eps, void *stream)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    if (!X || !G || !std::isfinite(eps)) return SVGD_ERR_INVALID_ARG;
+    rc = check_shape(c, n, D);
+    if (rc) return rc;
+    if (overlaps(X, G, n, D)) return SVGD_ERR_INVALID_ARG;
+    DeviceGuard guard(c->device);
+    hipStream_t s = (hipStream_t)stream;
+    rc = run_kernel_matrix(c, X, n, D, s);
+    if (rc) return rc;
+    return run_update<false>(c, X, G, nullptr, n, D, eps, s);
+}
+
+int svgd_phi(svgd_handle_t c, const float *X, const float *G, int n, int64_t D, float *PHI, void *stream)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    if (!X || !G || !PHI) return SVGD_ERR_INVALID_ARG;
+    rc = check_shape(c, n, D);
+    if (rc) return rc;
+    if (overlaps(X, PHI, n, D) || overlaps(G, PHI, n, D)) return SVGD_ERR_INVALID_ARG;
+    DeviceGuard guard(c->device);
+    hipStream_t s = (hipStream_t)stream;
+    rc = run_kernel_matrix(c, X, n, D, s);
+    if (rc) return rc;
+    return run_update<true>(c, const_cast<float *>(X), G, PHI, n, D, 0.f, s);
+}
+
+int svgd_get_last(svgd_handle_t c, double *h_out, float *K_host, void *stream)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    if (c->last_n < 1) return SVGD_ERR_INVALID_ARG;
+    DeviceGuard guard(c->device);
+    hipStream_t s = (hipStream_t)stream;
+    hipError_t e = hipSuccess;
+    if (h_out) e = hipMemcpyAsync(h_out, &c->state->h, sizeof(double), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess && K_host)
+        e = hipMemcpyAsync(K_host, c->coef + kOffK, (size_t)c->last_n * c->last_n * sizeof(float),
+                           hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(c, e);
+    return SVGD_OK;
+}
+
+int svgd_destroy(svgd_handle_t c)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    {
+        std::lock_guard<std::mutex> lock(g_live_mutex);
+        live_handles().erase(c);
+    }
+    c->magic = 0;
+    hipError_t e = hipSuccess, t;
+    {
+        DeviceGuard guard(c->device);
+        if ((t = hipFree(c->partials)) != hipSuccess) e = t;
+        if ((t = hipFree(c->part2)) != hipSuccess) e = t;
+        if ((t = hipFree(c->state)) != hipSuccess) e = t;
+        if ((t = hipFree(c->coef)) != hipSuccess) e = t;
+    }
+    delete c;
+    return e == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
+}
+
+int svgd_last_device_error(svgd_handle_t c)
+{
+    if (check_handle(c)) return 0;
+    return c->last_hip_error;
+}
+
+const char *svgd_status_string(int status)
+{
+    switch (status) {
+    case SVGD_OK: return "SVGD_OK";
+    case SVGD_ERR_INVALID_ARG: return "SVGD_ERR_INVALID_ARG";
+    case SVGD_ERR_BAD_HANDLE: return "SVGD_ERR_BAD_HANDLE";
+    case SVGD_ERR_TOO_LARGE: return "SVGD_ERR_TOO_LARGE";
+    case SVGD_ERR_ALLOC: return "SVGD_ERR_ALLOC";
+    case SVGD_ERR_DEVICE: return "SVGD_ERR_DEVICE";
+    default: return "SVGD_ERR_UNKNOWN";
+    }
+}
+
+} // extern "C"

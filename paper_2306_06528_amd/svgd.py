@@ -1,0 +1,136 @@
+"""Python binding of the C-ABI SVGD library (include/svgd.h): argument marshalling only.
+
+Every step of the method runs in the HIP kernels of libsvgd.so; torch tensors are used here
+only as owners of device memory and for the current stream.  Importing this module fails
+loudly if the built library is missing - there is no fallback path.
+"""
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsvgd.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -m paper_2306_06528_amd.build, or "
+        "__graft_entry__.build()); there is no fallback implementation")
+_lib = ctypes.CDLL(LIB_PATH)
+
+_H = ctypes.c_void_p
+_lib.svgd_create.argtypes = [ctypes.POINTER(_H), ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32]
+_lib.svgd_set_bandwidth.argtypes = [_H, ctypes.c_double]
+_lib.svgd_bandwidth.argtypes = [_H, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+                                ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+_lib.svgd_step.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+                           ctypes.c_float, ctypes.c_void_p]
+_lib.svgd_phi.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+                          ctypes.c_void_p, ctypes.c_void_p]
+_lib.svgd_get_last.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p, ctypes.c_void_p]
+_lib.svgd_destroy.argtypes = [_H]
+_lib.svgd_last_device_error.argtypes = [_H]
+_lib.svgd_status_string.argtypes = [ctypes.c_int]
+_lib.svgd_status_string.restype = ctypes.c_char_p
+for _f in ("svgd_create", "svgd_set_bandwidth", "svgd_bandwidth", "svgd_step", "svgd_phi",
+           "svgd_get_last", "svgd_destroy", "svgd_last_device_error"):
+    getattr(_lib, _f).restype = ctypes.c_int
+
+SVGD_OK = 0
+MAX_PARTICLES = 64
+
+
+class SvgdError(RuntimeError):
+    def __init__(self, status, hip_error=0):
+        self.status = status
+        self.hip_error = hip_error
+        name = _lib.svgd_status_string(status).decode()
+        super().__init__(f"{name} ({status})" + (f", hipError {hip_error}" if hip_error else ""))
+
+
+def status_string(status: int) -> str:
+    return _lib.svgd_status_string(status).decode()
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev_matrix(t: torch.Tensor, name: str):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.float32 and t.dim() == 2
+            and t.is_contiguous()):
+        raise TypeError(f"{name} must be a contiguous 2-D float32 CUDA tensor")
+    return t
+
+
+class Svgd:
+    """Handle of the library: svgd_create on construction, svgd_destroy on close()."""
+
+    def __init__(self, max_n: int, max_D: int, device: int = -1):
+        self._h = _H()
+        rc = _lib.svgd_create(ctypes.byref(self._h), int(max_n), int(max_D), int(device), 0)
+        if rc != SVGD_OK:
+            self._h = _H()
+            raise SvgdError(rc)
+
+    def _check(self, rc):
+        if rc != SVGD_OK:
+            raise SvgdError(rc, _lib.svgd_last_device_error(self._h))
+
+    def set_bandwidth(self, h_fixed: float):
+        self._check(_lib.svgd_set_bandwidth(self._h, float(h_fixed)))
+
+    def bandwidth(self, X, want_h=True, stream=None):
+        X = _dev_matrix(X, "X")
+        n, D = X.shape
+        out = ctypes.c_double(0.0)
+        self._check(_lib.svgd_bandwidth(self._h, X.data_ptr(), n, D,
+                                        ctypes.byref(out) if want_h else None, _stream_ptr(stream)))
+        return out.value if want_h else None
+
+    def step(self, X, G, eps: float, stream=None):
+        X, G = _dev_matrix(X, "X"), _dev_matrix(G, "G")
+        if X.shape != G.shape:
+            raise ValueError("X and G must have the same shape")
+        n, D = X.shape
+        self._check(_lib.svgd_step(self._h, X.data_ptr(), G.data_ptr(), n, D, float(eps),
+                                   _stream_ptr(stream)))
+
+    def phi(self, X, G, PHI, stream=None):
+        X, G, PHI = _dev_matrix(X, "X"), _dev_matrix(G, "G"), _dev_matrix(PHI, "PHI")
+        if X.shape != G.shape or X.shape != PHI.shape:
+            raise ValueError("X, G and PHI must have the same shape")
+        n, D = X.shape
+        self._check(_lib.svgd_phi(self._h, X.data_ptr(), G.data_ptr(), n, D, PHI.data_ptr(),
+                                  _stream_ptr(stream)))
+
+    def get_last(self, n: int, stream=None):
+        """(h, K) of the most recent call; K is an (n, n) float32 numpy array."""
+        import numpy as np
+        K = np.empty((n, n), np.float32)
+        h = ctypes.c_double(0.0)
+        self._check(_lib.svgd_get_last(self._h, ctypes.byref(h), K.ctypes.data_as(ctypes.c_void_p),
+                                       _stream_ptr(stream)))
+        return h.value, K
+
+    def close(self):
+        if self._h:
+            rc = _lib.svgd_destroy(self._h)
+            self._h = _H()
+            if rc != SVGD_OK:
+                raise SvgdError(rc)
+
+    def __enter__(self):
+        return self
+
+    def __exit__(self, *exc):
+        self.close()
+
+    def __del__(self):
+        try:
+            if self._h:
+                _lib.svgd_destroy(self._h)
+                self._h = _H()
+        except Exception:
+            pass

@@ -1,0 +1,61 @@
+"""Error behaviour of the C ABI with a live handle (needs the GPU for svgd_create)."""
+import ctypes
+
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mod():
+    assert torch.cuda.is_available()
+    from paper_2306_06528_amd import svgd
+    return svgd
+
+
+def test_argument_errors(mod):
+    lib = mod._lib
+    X = torch.randn(4, 100, device="cuda")
+    G = torch.randn(4, 100, device="cuda")
+    P = torch.empty(4, 100, device="cuda")
+    eng = mod.Svgd(4, 100)
+    h = eng._h
+    xp, gp, pp = X.data_ptr(), G.data_ptr(), P.data_ptr()
+    assert lib.svgd_step(h, None, gp, 4, 100, 0.1, None) == -1
+    assert lib.svgd_step(h, xp, None, 4, 100, 0.1, None) == -1
+    assert lib.svgd_step(h, xp, gp, 0, 100, 0.1, None) == -1
+    assert lib.svgd_step(h, xp, gp, 4, 0, 0.1, None) == -1
+    assert lib.svgd_step(h, xp, gp, 4, 100, float("nan"), None) == -1
+    assert lib.svgd_step(h, xp, gp, 4, 100, float("inf"), None) == -1
+    assert lib.svgd_step(h, xp, xp, 4, 100, 0.1, None) == -1            # X aliases G
+    assert lib.svgd_step(h, xp, xp + 400, 4, 100, 0.1, None) == -1      # partial overlap
+    assert lib.svgd_step(h, xp, gp, 5, 100, 0.1, None) == -3
+    assert lib.svgd_step(h, xp, gp, 4, 101, 0.1, None) == -3
+    assert lib.svgd_phi(h, xp, gp, 4, 100, xp, None) == -1              # PHI aliases X
+    assert lib.svgd_phi(h, xp, gp, 4, 100, None, None) == -1
+    assert lib.svgd_bandwidth(h, None, 4, 100, None, None) == -1
+    assert lib.svgd_get_last(h, None, None, None) == -1                 # nothing computed yet
+    assert lib.svgd_set_bandwidth(h, float("nan")) == -1
+    torch.cuda.synchronize()
+    assert torch.isfinite(X).all()
+    # a valid call still works afterwards, and the handle dies with destroy
+    assert lib.svgd_phi(h, xp, gp, 4, 100, pp, None) == 0
+    torch.cuda.synchronize()
+    assert torch.isfinite(P).all()
+    stale = ctypes.c_void_p(h.value)
+    eng.close()
+    assert lib.svgd_step(stale, xp, gp, 4, 100, 0.1, None) == -2        # use after destroy
+    assert lib.svgd_destroy(stale) == -2
+
+
+def test_binding_raises(mod):
+    eng = mod.Svgd(4, 100)
+    X = torch.randn(5, 100, device="cuda")
+    with pytest.raises(mod.SvgdError):
+        eng.step(X, torch.randn_like(X), 0.1)
+    with pytest.raises(TypeError):
+        eng.step(X.cpu(), X.cpu(), 0.1)
+    eng.close()
+    with pytest.raises(mod.SvgdError):
+        mod.Svgd(65, 100)

@@ -1,0 +1,290 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element.
+
+Tolerances (the stated bar): max|dphi| / max|phi| <= 1e-4, |dh| / h <= 1e-5, max|dK| <= 1e-5.
+Because eps*phi is only a few ulp of X at NN-like scales, phi is compared through the emit-phi
+variant of the same kernels (svgd_phi), and the in-place path (svgd_step) is then checked
+against fl32(x + eps * phi_gpu) to one ulp.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import svgd_oracle as orc
+from paper_2306_06528_amd import workloads
+
+pytestmark = pytest.mark.gpu
+
+TOL_PHI, TOL_H, TOL_K = 1e-4, 1e-5, 1e-5
+
+
+@pytest.fixture(scope="module")
+def svgd():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    from paper_2306_06528_amd import svgd as mod   # raises if libsvgd.so is missing
+    return mod
+
+
+def _ulp_diff(a, b):
+    """max distance in units of fp32 ulp of b."""
+    a = a.astype(np.float64)
+    b32 = b.astype(np.float32)
+    ulp = np.spacing(np.abs(b32)).astype(np.float64)
+    return float((np.abs(a - b32.astype(np.float64)) / ulp).max())
+
+
+def check_one_step(svgd, X0, G, eps, h_fixed=0.0, tol_phi=TOL_PHI):
+    """Runs svgd_phi and svgd_step on (X0, G) and compares with the oracle.  Returns errors."""
+    n, D = X0.shape
+    Xh, Gh = X0.cpu().numpy(), G.cpu().numpy()
+    ref = orc.step(Xh, Gh, eps, h_fixed=h_fixed, want_xnew=False)
+    PHI = torch.full_like(X0, float("nan"))
+    X = X0.clone()
+    with svgd.Svgd(n, D) as eng:
+        if h_fixed > 0:
+            eng.set_bandwidth(h_fixed)
+        h_bw = eng.bandwidth(X)
+        eng.phi(X, G, PHI)
+        h, K = eng.get_last(n)
+        assert torch.equal(X, X0), "svgd_phi must leave X untouched"
+        eng.step(X, G, eps)
+        torch.cuda.synchronize()
+    assert h_bw == h
+    phi = PHI.cpu().numpy().astype(np.float64)
+    assert np.isfinite(phi).all()
+    scale = np.abs(ref["phi"]).max()
+    e_phi = np.abs(phi - ref["phi"]).max() / (scale if scale > 0 else 1.0)
+    e_l2 = np.linalg.norm(phi - ref["phi"]) / max(np.linalg.norm(ref["phi"]), 1e-300)
+    e_h = abs(h - ref["h"]) / ref["h"]
+    e_K = np.abs(K.astype(np.float64) - ref["K"]).max()
+    assert e_h <= TOL_H, f"h: {h} vs {ref['h']} (rel {e_h:.3e})"
+    assert e_K <= TOL_K, f"K: max abs err {e_K:.3e}"
+    assert np.array_equal(K, K.T) and np.all(np.diag(K) == 1.0)
+    assert e_phi <= tol_phi, f"phi: max err / max|phi| = {e_phi:.3e} (l2 rel {e_l2:.3e})"
+    # in-place path: x_new = fl32(fma(eps, phi_gpu, x_old)), allow 1 ulp
+    want = Xh.astype(np.float64) + np.float64(np.float32(eps)) * phi
+    ulps = _ulp_diff(want, X.cpu().numpy())
+    assert ulps <= 1.0, f"in-place update differs from x + eps*phi by {ulps} ulp"
+    return dict(e_phi=e_phi, e_l2=e_l2, e_h=e_h, e_K=e_K)
+
+
+def _random_problem(n, D, seed, x_std=1.0, device="cuda"):
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    X = torch.randn(n, D, generator=g, device=device) * x_std
+    G = torch.randn(n, D, generator=g, device=device)
+    return X, G
+
+
+# every particle count takes its own template instance / row masking: cover them all at one
+# ragged D, and a set of D around the tile sizes (4, 64, 128, 256 columns) at a few n.
+@pytest.mark.parametrize("n", list(range(1, 18)) + [24, 31, 32, 33, 47, 48, 49, 63, 64])
+def test_every_particle_count(svgd, n):
+    X, G = _random_problem(n, 1531, 1000 + n)
+    check_one_step(svgd, X, G, 0.01)
+
+
+@pytest.mark.parametrize("n", [1, 2, 4, 8, 13, 16, 20, 32, 40, 64])
+@pytest.mark.parametrize("D", [1, 2, 3, 4, 5, 63, 64, 65, 127, 128, 129, 255, 257, 1024, 8577, 70001])
+def test_ragged_lengths(svgd, n, D):
+    X, G = _random_problem(n, D, 7 * n + D)
+    if n > 1 and D < 4:
+        # few columns: d2 can be tiny relative to |x|^2; keep the problem well conditioned
+        X = X * 3.0
+    check_one_step(svgd, X, G, 0.05)
+
+
+@pytest.mark.parametrize("n", [4, 8, 16, 32, 64])
+def test_many_tiles(svgd, n):
+    """Several persistent-grid iterations per workgroup and a ragged tail."""
+    D = 3_000_017 if n <= 16 else 1_000_003
+    X, G = _random_problem(n, D, 99 + n, x_std=0.02)
+    G = G * 1e-3
+    check_one_step(svgd, X, G, 1e-4)
+
+
+@pytest.mark.parametrize("n", [3, 8, 16, 32, 64])
+def test_translated_particles(svgd, n):
+    """A common offset 10x the spread must not spoil d2 (centred / direct-difference Gram)."""
+    X, G = _random_problem(n, 4099, 5 + n)
+    t = torch.full((1, 4099), 10.0, device="cuda")
+    check_one_step(svgd, X + t, G, 0.01, tol_phi=TOL_PHI)
+
+
+def test_coincident_particles(svgd):
+    """All particles equal: med = 0 -> h = 1, K = 1, phi_i = mean_j g_j."""
+    x = torch.randn(1, 301, device="cuda")
+    for n in (2, 5, 16, 32):
+        X = x.repeat(n, 1).contiguous()
+        G = torch.randn(n, 301, device="cuda")
+        PHI = torch.empty_like(X)
+        with svgd.Svgd(n, 301) as eng:
+            eng.phi(X, G, PHI)
+            h, K = eng.get_last(n)
+        assert h == 1.0 and np.all(K == 1.0)
+        want = G.double().mean(0, keepdim=True).repeat(n, 1)
+        err = (PHI.double() - want).abs().max().item() / want.abs().max().item()
+        assert err <= TOL_PHI
+
+
+def test_single_particle_is_gradient_ascent(svgd):
+    X, G = _random_problem(1, 1000, 3)
+    X0 = X.clone()
+    with svgd.Svgd(1, 1000) as eng:
+        eng.step(X, G, 0.25)
+        h, K = eng.get_last(1)
+    assert h == 1.0 and K.tolist() == [[1.0]]
+    want = torch.addcmul(X0, G, torch.tensor(0.25, device="cuda"))
+    assert _ulp_diff(want.cpu().numpy().astype(np.float64), X.cpu().numpy()) <= 1.0
+
+
+@pytest.mark.parametrize("n", [4, 16, 32])
+def test_fixed_bandwidth(svgd, n):
+    """The paper's fixed-lengthscale kernel: h = 2 l^2 given, no median."""
+    X, G = _random_problem(n, 2049, 17 + n, x_std=0.1)
+    ell = 4.0
+    check_one_step(svgd, X, G, 1e-3, h_fixed=2 * ell * ell)
+
+
+def test_handle_reuse_across_shapes(svgd):
+    """One handle, several (n, D) in a row: no state leaks from one call to the next."""
+    with svgd.Svgd(64, 50_000) as eng:
+        for n, D in ((64, 50_000), (3, 17), (32, 4097), (8, 50_000), (17, 129)):
+            X, G = _random_problem(n, D, n * D % 1000)
+            PHI = torch.empty_like(X)
+            eng.phi(X, G, PHI)
+            h, K = eng.get_last(n)
+            ref = orc.step(X.cpu().numpy(), G.cpu().numpy(), 0.0, want_xnew=False)
+            assert abs(h - ref["h"]) / ref["h"] <= TOL_H
+            assert np.abs(K - ref["K"]).max() <= TOL_K
+            e = np.abs(PHI.cpu().numpy() - ref["phi"]).max() / np.abs(ref["phi"]).max()
+            assert e <= TOL_PHI
+
+
+def test_stream_argument(svgd):
+    """Work is enqueued on the stream that is passed in."""
+    X, G = _random_problem(8, 100_000, 21)
+    X0 = X.clone()
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with svgd.Svgd(8, 100_000) as eng:
+        with torch.cuda.stream(s):
+            eng.step(X, G, 0.01, stream=s)
+        s.synchronize()
+    ref = orc.step(X0.cpu().numpy(), G.cpu().numpy(), 0.01)
+    err = np.abs(X.cpu().numpy() - ref["X_new"]).max() / np.abs(ref["X_new"]).max()
+    assert err <= 1e-6
+
+
+# ----------------------------------------------------------------------------------------------
+# the five workloads
+# ----------------------------------------------------------------------------------------------
+def test_config1_tiny_trajectory(svgd):
+    """n=4, D=1024, 200 steps on N(mu, I): teacher-forced parity every step, free-running
+    drift at the end, and the particle mean converging to mu."""
+    wl = workloads.make(1, device="cuda")
+    X = wl.X0.clone()
+    Xref = wl.X0.cpu().numpy().astype(np.float64)
+    mu = wl.mu.cpu().numpy().astype(np.float64)
+    n, D = X.shape
+    PHI = torch.empty_like(X)
+    err0 = np.linalg.norm(Xref.mean(0) - mu)
+    with svgd.Svgd(n, D) as eng:
+        for step in range(wl.cfg.steps):
+            G = wl.score(X, step)
+            eng.phi(X, G, PHI)
+            h, K = eng.get_last(n)
+            ref = orc.step(X.cpu().numpy(), G.cpu().numpy(), wl.cfg.eps, want_xnew=False)
+            assert abs(h - ref["h"]) / ref["h"] <= TOL_H
+            assert np.abs(K - ref["K"]).max() <= TOL_K
+            e = np.abs(PHI.cpu().numpy() - ref["phi"]).max() / np.abs(ref["phi"]).max()
+            assert e <= TOL_PHI, f"step {step}: {e:.3e}"
+            eng.step(X, G, wl.cfg.eps)
+            Xref = orc.step(Xref, -(Xref - mu), wl.cfg.eps, want_phi=False)["X_new"]
+    Xg = X.cpu().numpy().astype(np.float64)
+    drift = np.abs(Xg - Xref).max() / np.abs(Xref).max()
+    assert drift <= 1e-4, f"free-running drift {drift:.3e}"
+    err = np.linalg.norm(Xg.mean(0) - mu)
+    assert err / math.sqrt(D) <= 0.05 and err < 0.1 * err0
+
+
+def test_config2_pinn_mlp_trajectory(svgd):
+    """n=16, D=8577 (odd D: rows only 4-byte aligned), 1000 steps; parity checked every 50."""
+    wl = workloads.make(2, device="cuda")
+    X = wl.X0.clone()
+    n, D = X.shape
+    PHI = torch.empty_like(X)
+    Xref = wl.X0.cpu().numpy().astype(np.float64)
+    mu = wl.mu.cpu().numpy().astype(np.float64)
+    is2 = wl.inv_sigma2.cpu().numpy().astype(np.float64)
+    with svgd.Svgd(n, D) as eng:
+        for step in range(wl.cfg.steps):
+            G = wl.score(X, step)
+            if step % 50 == 0 or step == wl.cfg.steps - 1:
+                eng.phi(X, G, PHI)
+                h, K = eng.get_last(n)
+                ref = orc.step(X.cpu().numpy(), G.cpu().numpy(), wl.cfg.eps, want_xnew=False)
+                assert abs(h - ref["h"]) / ref["h"] <= TOL_H
+                assert np.abs(K - ref["K"]).max() <= TOL_K
+                e = np.abs(PHI.cpu().numpy() - ref["phi"]).max() / np.abs(ref["phi"]).max()
+                assert e <= TOL_PHI, f"step {step}: {e:.3e}"
+            eng.step(X, G, wl.cfg.eps)
+            if step < 100:   # free-running oracle for the first 100 steps
+                Xref = orc.step(Xref, (mu - Xref) * is2, wl.cfg.eps, want_phi=False)["X_new"]
+                if step == 99:
+                    drift = np.abs(X.cpu().numpy() - Xref).max() / np.abs(Xref).max()
+                    assert drift <= 1e-4, f"free-running drift after 100 steps {drift:.3e}"
+
+
+def _full_size_check(svgd, cfg_index, nchunks=6, chunk=4096):
+    """Full-size config in the launch configuration the benchmark times: h and K against the
+    oracle's full d2; phi on sampled column chunks (start, middle, ragged end)."""
+    wl = workloads.make(cfg_index, device="cuda")
+    n, D = wl.n, wl.D
+    X = wl.X0.clone()
+    G = wl.score(X, 0)
+    PHI = torch.empty_like(X)
+    with svgd.Svgd(n, D) as eng:
+        eng.phi(X, G, PHI)
+        h, K = eng.get_last(n)
+        eng.step(X, G, wl.cfg.eps)
+        torch.cuda.synchronize()
+    Xh, Gh = wl.X0.cpu().numpy(), G.cpu().numpy()
+    d2 = orc.pairwise_d2(Xh)
+    h_ref = orc.bandwidth(d2)
+    K_ref, _ = orc.kernel(d2, h_ref)
+    assert abs(h - h_ref) / h_ref <= TOL_H, f"h {h} vs {h_ref}"
+    assert np.abs(K - K_ref).max() <= TOL_K
+    rng = np.random.default_rng(cfg_index)
+    starts = [0, D - chunk] + [int(s) for s in rng.integers(0, D - chunk, nchunks - 2)]
+    # max|phi| over the whole array from the GPU result (it is only the normaliser)
+    scale = float(PHI.abs().max().item())
+    Xn = X.cpu().numpy()
+    PHIh = PHI.cpu().numpy()
+    worst = 0.0
+    for s in starts:
+        ref = orc.phi_cols(Xh, Gh, K_ref, h_ref, s, chunk)
+        got = PHIh[:, s:s + chunk].astype(np.float64)
+        worst = max(worst, np.abs(got - ref).max() / scale)
+        assert np.abs(got - ref).max() / np.abs(ref).max() <= TOL_PHI * 10  # chunk-local sanity
+        want = Xh[:, s:s + chunk].astype(np.float64) + np.float64(np.float32(wl.cfg.eps)) * got
+        assert _ulp_diff(want, Xn[:, s:s + chunk]) <= 1.0
+    assert worst <= TOL_PHI, f"phi err / max|phi| = {worst:.3e}"
+    # properties that hold at any size: columns are independent, so the whole update equals
+    # x + eps*phi everywhere (checked on the device, all n*D entries)
+    want_all = torch.addcmul(wl.X0.double(), PHI.double(),
+                             torch.tensor(float(np.float32(wl.cfg.eps)), device="cuda", dtype=torch.float64))
+    assert (X.double() - want_all).abs().max().item() <= 2.0 * float(np.spacing(np.float32(wl.X0.abs().max().item())))
+
+
+def test_config3_operator_net_full_size(svgd):
+    _full_size_check(svgd, 3)
+
+
+def test_config4_resnet18_full_size(svgd):
+    _full_size_check(svgd, 4)
+
+
+def test_config5_large_ensemble_full_size(svgd):
+    _full_size_check(svgd, 5)
