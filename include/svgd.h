@@ -92,6 +92,23 @@ int svgd_phi(svgd_handle_t h, const float *X, const float *G, int n, int64_t D, 
  */
 int svgd_get_last(svgd_handle_t h, double *h_out, float *K_host, void *stream);
 
+/*
+ * Per-kernel timing for benchmarks.  Between svgd_profile_begin and svgd_profile_end every kernel
+ * launched through this handle is bracketed by a pair of HIP events on the stream it is launched
+ * on.  svgd_profile_end waits for those events and fills ms_sum[k] / count[k] (HOST arrays of
+ * SVGD_KERNEL_KINDS entries) with the total elapsed milliseconds and the number of launches of
+ * kernel kind k, then switches recording off.  At most 8192 launches are recorded per session.
+ */
+enum svgd_kernel_kind {
+    SVGD_KERNEL_GRAM = 0,      /* pairwise-d2 partial sums (pass over X) */
+    SVGD_KERNEL_REDUCE = 1,    /* fp64 reduction of the partials */
+    SVGD_KERNEL_BANDWIDTH = 2, /* median, h, K, coefficient tables */
+    SVGD_KERNEL_UPDATE = 3,    /* fused update (pass over X and G, X written) */
+    SVGD_KERNEL_KINDS = 4
+};
+int svgd_profile_begin(svgd_handle_t h);
+int svgd_profile_end(svgd_handle_t h, double *ms_sum, int *count);
+
 /* Free the handle's scratch and invalidate the handle.  The caller synchronises beforehand. */
 int svgd_destroy(svgd_handle_t h);
 

@@ -9,11 +9,12 @@
 namespace svgd {
 
 constexpr int kBwThreads = 1024;
+constexpr int kSlices = 32; // slices of the partial reduction (see reduce_partials_kernel)
 
 __device__ inline int pair_index(int i, int j, int n) { return i * n - (i * (i + 1)) / 2 + (j - i - 1); } // i < j
 
 __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__restrict__ part2,
-                                                               int nslices, int n, int mode,
+                                                               int n, int mode,
                                                                double h_fixed,
                                                                DevState *__restrict__ st,
                                                                float *__restrict__ coef)
@@ -27,9 +28,15 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
     const int P = n * (n + 1) / 2;
     const int Pp = n * (n - 1) / 2;
 
+    // part2 always holds kSlices slices (empty ones are zero): a fixed trip count lets all the
+    // loads of one entry issue together instead of one latency after the other
     for (int p = tid; p < P; p += kBwThreads) {
+        double v[kSlices];
+#pragma unroll
+        for (int k = 0; k < kSlices; ++k) v[k] = part2[(int64_t)k * P + p];
         double s = 0.0;
-        for (int k = 0; k < nslices; ++k) s += part2[(int64_t)k * P + p];
+#pragma unroll
+        for (int k = 0; k < kSlices; ++k) s += v[k];
         S[p] = s;
     }
     if (tid < 2) sel[tid] = 0.0;
@@ -53,22 +60,34 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
 
     // Median of the multiset of all n*n entries of d2: n diagonal zeros plus every pair value
     // twice.  Sorted position t of the full list is 0 for t < n and the ((t-n)/2)-th smallest
-    // pair value otherwise; an even count averages positions n*n/2 - 1 and n*n/2.  The two
-    // order statistics are found by rank counting (ties broken by index).
+    // pair value otherwise; an even count averages positions n*n/2 - 1 and n*n/2.  The pair
+    // values are sorted by a bitonic network in LDS (S is free by now and serves as the buffer;
+    // padded with +inf to a power of two).
     if (h_fixed <= 0.0 && Pp > 0) {
-        const int n2 = n * n;
-        const int t_lo = (n2 - 1) / 2, t_hi = n2 / 2;
-        const int k_lo = (t_lo >= n) ? (t_lo - n) / 2 : -1;
-        const int k_hi = (t_hi >= n) ? (t_hi - n) / 2 : -1;
-        for (int e = tid; e < Pp; e += kBwThreads) {
-            const double v = pr[e];
-            int rank = 0;
-            for (int f = 0; f < Pp; ++f) {
-                const double w = pr[f];
-                rank += (w < v || (w == v && f < e)) ? 1 : 0;
+        int M = 1;
+        while (M < Pp) M <<= 1;
+        for (int e = tid; e < M; e += kBwThreads) S[e] = (e < Pp) ? pr[e] : __builtin_huge_val();
+        __syncthreads();
+        for (int k = 2; k <= M; k <<= 1) {
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int e = tid; e < (M >> 1); e += kBwThreads) {
+                    const int a = ((e & ~(j - 1)) << 1) | (e & (j - 1)); // bit j clear
+                    const int b2 = a | j;
+                    const double va = S[a], vb = S[b2];
+                    const bool up = ((a & k) == 0);
+                    if ((va > vb) == up) {
+                        S[a] = vb;
+                        S[b2] = va;
+                    }
+                }
+                __syncthreads();
             }
-            if (rank == k_lo) sel[0] = v;
-            if (rank == k_hi) sel[1] = v;
+        }
+        if (tid == 0) {
+            const int n2 = n * n;
+            const int t_lo = (n2 - 1) / 2, t_hi = n2 / 2;
+            sel[0] = (t_lo >= n) ? S[(t_lo - n) / 2] : 0.0;
+            sel[1] = (t_hi >= n) ? S[(t_hi - n) / 2] : 0.0;
         }
     }
     __syncthreads();

@@ -93,6 +93,7 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
 //   3. writes the slab to a wave-private LDS region with a 16-byte-granule XOR swizzle,
 //   4. reads it back as v_mfma_f32_16x16x4_f32 operands: lane (q = lane/16, rr = lane%16) takes
 //      row 16b+rr, 4 columns per read; the 4 k-slots of one MFMA are columns {16s+4q+c, q=0..3},
+//      (the loads of the next slab are issued here, before the multiply phase),
 //   5. issues one MFMA per unordered block pair (b <= b'), fp32 accumulators in registers:
 //      lane (q, c), register r of pair (b, b') holds S[16b + 4q + r][16b' + c].
 // Any assignment of columns to k-slots is valid because every column is summed exactly once.
@@ -116,16 +117,19 @@ __global__ __launch_bounds__(128) void gram_mfma_kernel(const float *__restrict_
     for (int p = 0; p < NPAIR; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     const int64_t ntile = (D + 127) >> 7;
-    for (int64_t tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+    f32x4 x[RPL];
+    auto load_slab = [&](int64_t tile) {
         const int64_t wcol = (tile << 7) + (wave << 6);
         const int64_t col = wcol + 4 * c16;
         const bool full = (wcol + 64 <= D);
-        f32x4 x[RPL];
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int row = 4 * i + q;
             x[i] = (row < n) ? load4(X + (int64_t)row * D, col, D, full) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
+    };
+    if ((int64_t)blockIdx.x < ntile) load_slab(blockIdx.x);
+    for (int64_t tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
         f32x4 s = x[0];
 #pragma unroll
         for (int i = 1; i < RPL; ++i) s += x[i];
@@ -144,6 +148,8 @@ __global__ __launch_bounds__(128) void gram_mfma_kernel(const float *__restrict_
             *reinterpret_cast<f32x4 *>(&my[row * 64 + ((c16 ^ (row & 15)) << 2)]) = x[i] - s;
         }
         __syncthreads();
+        // the next slab's loads are in flight while this one is multiplied
+        if (tile + gridDim.x < ntile) load_slab(tile + gridDim.x);
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             f32x4 a[NB];
@@ -198,14 +204,15 @@ __global__ __launch_bounds__(128) void gram_mfma_kernel(const float *__restrict_
     }
 }
 
-// Sum the per-workgroup fp32 partials in fp64, split into `nslices` interleaved slices so that
-// many threads share the work: part2[slice][p] = sum_{k = slice (mod nslices)} partials[k][p].
+// Sum the per-workgroup fp32 partials in fp64, split into gridDim.y interleaved slices so that
+// many threads share the work: part2[slice][p] = sum_{k = slice (mod nslices)} partials[k][p]
+// (zero for a slice with no partials).
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ partials,
-                                                              int nparts, int P, int nslices,
+                                                              int nparts, int P,
                                                               double *__restrict__ part2)
 {
     const int p = blockIdx.x * 256 + threadIdx.x;
-    const int slice = blockIdx.y;
+    const int slice = blockIdx.y, nslices = gridDim.y;
     if (p >= P) return;
     double s = 0.0;
     for (int k = slice; k < nparts; k += nslices) s += (double)partials[(int64_t)k * P + p];

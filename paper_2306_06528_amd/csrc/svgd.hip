@@ -6,6 +6,7 @@
 #include <mutex>
 #include <new>
 #include <unordered_set>
+#include <vector>
 
 #include "bandwidth_kernels.hpp"
 #include "common.hpp"
@@ -18,7 +19,6 @@ namespace {
 
 constexpr uint32_t kMagic = 0x53564744u; // "SVGD"
 constexpr int kMaxParts = 2048;          // upper bound on Gram workgroups (= partial vectors)
-constexpr int kMaxSlices = 32;
 
 } // namespace
 
@@ -32,9 +32,13 @@ struct svgd_ctx {
     int last_n; // 0 = nothing computed yet
     int last_hip_error;
     float *partials;  // [kMaxParts][P]
-    double *part2;    // [kMaxSlices][P]
+    double *part2;    // [kSlices][P]
     DevState *state;
     float *coef;      // kCoefFloats
+    // optional per-kernel timing (svgd_profile_begin/end): event pairs recorded around launches
+    bool profiling;
+    std::vector<hipEvent_t> ev_pool; // 2 events per record
+    std::vector<int> ev_kind;        // SVGD_KERNEL_* of each record
 };
 
 namespace {
@@ -74,6 +78,32 @@ int check_handle(svgd_ctx *c)
     if (!live_handles().count(c) || c->magic != kMagic) return SVGD_ERR_BAD_HANDLE;
     return SVGD_OK;
 }
+
+constexpr size_t kMaxProfileRecords = 8192;
+
+// Records a start event on construction and a stop event on destruction when profiling is on.
+struct KernelTimer {
+    svgd_ctx *c;
+    hipStream_t s;
+    size_t slot = (size_t)-1;
+    KernelTimer(svgd_ctx *ctx, int kind, hipStream_t stream) : c(ctx), s(stream)
+    {
+        if (!c->profiling || c->ev_kind.size() >= kMaxProfileRecords) return;
+        const size_t idx = c->ev_kind.size();
+        while (c->ev_pool.size() < 2 * (idx + 1)) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return; }
+            c->ev_pool.push_back(e);
+        }
+        if (hipEventRecord(c->ev_pool[2 * idx], s) != hipSuccess) { (void)hipGetLastError(); return; }
+        c->ev_kind.push_back(kind);
+        slot = idx;
+    }
+    ~KernelTimer()
+    {
+        if (slot != (size_t)-1) (void)hipEventRecord(c->ev_pool[2 * slot + 1], s);
+    }
+};
 
 int check_shape(svgd_ctx *c, int n, int64_t D)
 {
@@ -133,10 +163,12 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
         const int64_t ngroups = (D + 3) / 4;
         nparts = clampi((ngroups + 255) / 256, 1, c->num_cu * 4);
         mode = (n <= 8) ? kModeDiff : kModeGram;
+        KernelTimer t(c, SVGD_KERNEL_GRAM, s);
 #define CALL(N) launch_gram_valu<N>(X, D, c->partials, nparts, s)
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
     } else {
+        KernelTimer t(c, SVGD_KERNEL_GRAM, s);
         const int64_t ntile = (D + 127) / 128;
         nparts = clampi(ntile, 1, c->num_cu * 4);
         mode = kModeGram;
@@ -151,12 +183,17 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
 
-    const int nslices = nparts < kMaxSlices ? nparts : kMaxSlices;
-    reduce_partials_kernel<<<dim3((P + 255) / 256, nslices), 256, 0, s>>>(c->partials, nparts, P,
-                                                                         nslices, c->part2);
+    {
+        KernelTimer t(c, SVGD_KERNEL_REDUCE, s);
+        reduce_partials_kernel<<<dim3((P + 255) / 256, kSlices), 256, 0, s>>>(c->partials, nparts, P,
+                                                                             c->part2);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
-    bandwidth_kernel<<<1, kBwThreads, 0, s>>>(c->part2, nslices, n, mode, c->h_fixed, c->state, c->coef);
+    {
+        KernelTimer t(c, SVGD_KERNEL_BANDWIDTH, s);
+        bandwidth_kernel<<<1, kBwThreads, 0, s>>>(c->part2, n, mode, c->h_fixed, c->state, c->coef);
+    }
     e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
     c->last_n = n;
@@ -168,6 +205,7 @@ template <bool EMIT>
 int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, float eps,
                hipStream_t s)
 {
+    KernelTimer t(c, SVGD_KERNEL_UPDATE, s);
     if (n <= 16) {
         const int64_t ngroups = (D + 3) / 4;
         const int grid = clampi((ngroups + 255) / 256, 1, c->num_cu * 8);
@@ -175,15 +213,18 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
     } else {
-        const int64_t ntile = (D + 63) / 64;
-        const int grid = clampi((ntile + 3) / 4, 1, c->num_cu * 2);
+        // workers walk contiguous ranges of full 64-column tiles; one more workgroup does D mod 64
+        const int64_t nfull = D / 64;
+        const int grid = clampi((nfull + 3) / 4, 1, c->num_cu * 2) + 1;
         const int NB = (n + 15) / 16;
-        if (NB == 2)
-            update_mfma_kernel<2, EMIT><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps);
-        else if (NB == 3)
-            update_mfma_kernel<3, EMIT><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps);
-        else
-            update_mfma_kernel<4, EMIT><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps);
+#define UPD(NBV, FULL) update_mfma_kernel<NBV, EMIT, FULL><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps)
+        if (n == 32) UPD(2, true);
+        else if (n == 48) UPD(3, true);
+        else if (n == 64) UPD(4, true);
+        else if (NB == 2) UPD(2, false);
+        else if (NB == 3) UPD(3, false);
+        else UPD(4, false);
+#undef UPD
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
@@ -213,6 +254,7 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
     c->part2 = nullptr;
     c->state = nullptr;
     c->coef = nullptr;
+    c->profiling = false;
 
     hipError_t e;
     int dev = device_id;
@@ -232,7 +274,7 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
 
     const size_t P = (size_t)max_n * (max_n + 1) / 2;
     bool ok = hipMalloc(&c->partials, (size_t)kMaxParts * P * sizeof(float)) == hipSuccess &&
-              hipMalloc(&c->part2, (size_t)kMaxSlices * P * sizeof(double)) == hipSuccess &&
+              hipMalloc(&c->part2, (size_t)kSlices * P * sizeof(double)) == hipSuccess &&
               hipMalloc(&c->state, sizeof(DevState)) == hipSuccess &&
               hipMalloc(&c->coef, (size_t)kCoefFloats * sizeof(float)) == hipSuccess;
     if (!ok) {
@@ -328,6 +370,35 @@ int svgd_get_last(svgd_handle_t c, double *h_out, float *K_host, void *stream)
     return SVGD_OK;
 }
 
+int svgd_profile_begin(svgd_handle_t c)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    c->ev_kind.clear();
+    c->profiling = true;
+    return SVGD_OK;
+}
+
+int svgd_profile_end(svgd_handle_t c, double *ms_sum, int *count)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    if (!ms_sum || !count) return SVGD_ERR_INVALID_ARG;
+    c->profiling = false;
+    for (int k = 0; k < SVGD_KERNEL_KINDS; ++k) { ms_sum[k] = 0.0; count[k] = 0; }
+    DeviceGuard guard(c->device);
+    for (size_t r = 0; r < c->ev_kind.size(); ++r) {
+        hipError_t e = hipEventSynchronize(c->ev_pool[2 * r + 1]);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, c->ev_pool[2 * r], c->ev_pool[2 * r + 1]);
+        if (e != hipSuccess) { c->ev_kind.clear(); return fail(c, e); }
+        ms_sum[c->ev_kind[r]] += (double)ms;
+        count[c->ev_kind[r]] += 1;
+    }
+    c->ev_kind.clear();
+    return SVGD_OK;
+}
+
 int svgd_destroy(svgd_handle_t c)
 {
     int rc = check_handle(c);
@@ -344,6 +415,7 @@ int svgd_destroy(svgd_handle_t c)
         if ((t = hipFree(c->part2)) != hipSuccess) e = t;
         if ((t = hipFree(c->state)) != hipSuccess) e = t;
         if ((t = hipFree(c->coef)) != hipSuccess) e = t;
+        for (hipEvent_t ev : c->ev_pool) (void)hipEventDestroy(ev);
     }
     delete c;
     return e == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;

@@ -58,54 +58,139 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 
 // ---------------------------------------------------------------------------------------------
 // 16 < n <= 64: matrix cores, v_mfma_f32_16x16x4_f32 with M = output particle i, K = input
-// particle j, N = column.  A wave owns 16*NB rows x 64 columns per iteration:
-//   lane (q = lane/16, c = lane%16) loads, for b < NB and r < 4, row 16b + 4q + r at columns
-//   4c..4c+3 of the tile (256 B contiguous per row per quarter-wave).  Step s = 4b + r of the
-//   contraction feeds k-slot q with row 16b + 4q + r; the 4 components of the 16-byte load are
-//   4 independent N-tiles (tile t = columns {4c + t}).  The 16x16 result of output block bi puts
-//   row 16bi + 4q + r, column c in register r of lane (q, c) - exactly the rows this lane
-//   loaded, so x_old is already in place for the epilogue and nothing crosses lanes.
-// The A operands (C re-ordered, 4*NB*NB registers) are loaded once per wave; the grid is
-// persistent.  Rows >= n (n not a multiple of 16) are neither loaded nor stored; their A entries
-// are zero.
+// particle j, N = column.
+//
+// Register tile.  A wave owns 16*NB rows x 64 columns at a time: lane (q = lane/16, c = lane%16)
+// loads, for b < NB and r < 4, row 16b + 4q + r at columns 4c..4c+3 of the tile (256 B contiguous
+// per row per quarter-wave).  Step s = 4b + r of the contraction feeds k-slot q with row
+// 16b + 4q + r; the 4 components of the 16-byte load are 4 independent N-tiles (tile t = columns
+// {4c + t}).  The 16x16 result of output block bi puts row 16bi + 4q + r, column c in register r
+// of lane (q, c) - exactly the rows this lane loaded, so x_old is already in place for the
+// epilogue and nothing crosses lanes.  The A operands (C re-ordered by the bandwidth kernel) sit
+// in LDS, shared by the workgroup's 4 waves, and are re-read per output block.
+//
+// Stores.  A row starts at i*D floats, so for general D the rows are not 128-byte aligned and a
+// store of "the tile's columns" would cut cache lines in two for almost every row; partial-line
+// writes cost far more HBM time than they carry bytes.  Loads do not care.  So each wave
+//   - owns a CONTIGUOUS range of tiles and walks it left to right,
+//   - stages each finished 16-row output block in LDS (cur, 16 x 64 floats),
+//   - and for row i stores the 64-column window that ends r_i columns before the tile does,
+//     r_i = (address of row i at the tile's first column, in floats) mod 32: that window starts
+//     on a 128-byte boundary, and its first r_i columns are the previous tile's last ones, kept
+//     in LDS (carry, 64 x 32 floats per wave).
+// Every store instruction then writes whole cache lines.  Only the two ends of a wave's range
+// see partial lines: the first tile masks what lies left of the range, and the carry is flushed
+// element-wise after the last tile.  Columns beyond the last full tile (D mod 64) are done by
+// one extra workgroup with a plain loop.  Rows >= n (n not a multiple of 16) are neither loaded
+// nor stored; their A entries are zero.
 // ---------------------------------------------------------------------------------------------
-template <int NB, bool EMIT>
-__global__ __launch_bounds__(256) void update_mfma_kernel(float *__restrict__ X,
-                                                          const float *__restrict__ G,
-                                                          float *__restrict__ PHI,
-                                                          const float *__restrict__ coef,
-                                                          const DevState *__restrict__ st, int n,
-                                                          int64_t D, float eps)
+constexpr int kUpdCur = 16 * 64;    // floats per wave
+constexpr int kUpdCarry = 64 * 32;  // floats per wave
+
+template <bool EMIT>
+__device__ inline void update_tail_columns(float *__restrict__ X, const float *__restrict__ G,
+                                           float *__restrict__ OUT, const float *__restrict__ coef,
+                                           float c2h, int n, int64_t D, int64_t col0, float eps,
+                                           float *__restrict__ lds)
+{
+    // plain per-column evaluation for the < 64 columns after the last full tile
+    float *zs = lds, *xs = lds + 64 * 64;
+    const int col = threadIdx.x & 63, part = threadIdx.x >> 6;
+    const bool ok = (col0 + col < D);
+    for (int j = part; j < n; j += 4) {
+        float xv = 0.f, gv = 0.f;
+        if (ok) {
+            xv = X[(int64_t)j * D + col0 + col];
+            gv = G[(int64_t)j * D + col0 + col];
+        }
+        xs[j * 64 + col] = xv;
+        zs[j * 64 + col] = gv - c2h * xv;
+    }
+    __syncthreads();
+    for (int i = part; i < n; i += 4) {
+        float acc = 0.f;
+        for (int j = 0; j < n; ++j) acc = fmaf(coef[kOffC + i * n + j], zs[j * 64 + col], acc);
+        const float xv = xs[i * 64 + col];
+        const float phi = fmaf(coef[kOffRho + i], xv, acc);
+        if (ok) OUT[(int64_t)i * D + col0 + col] = EMIT ? phi : fmaf(eps, phi, xv);
+    }
+}
+
+// keeps the compiler from turning per-row addresses into 2 x 16 loop-carried pointer pairs
+__device__ inline void opaque(const float *&p) { asm volatile("" : "+v"(p)); }
+
+template <int NB, bool EMIT, bool FULLROWS>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
+                        const float *__restrict__ coef, const DevState *__restrict__ st, int n,
+                        int64_t D, float eps)
 {
     constexpr int NS = 4 * NB; // contraction steps = rows per lane
+    // [A operands: NB*NB*64 float4][4 waves x (cur + carry)]
+    __shared__ __attribute__((aligned(16))) float lds[NB * NB * 64 * 4 + 4 * (kUpdCur + kUpdCarry)];
     const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q = lane >> 4, c16 = lane & 15;
     const float c2h = st->two_over_h;
+    float *__restrict__ OUT = EMIT ? PHI : X;
 
-    float A[NB][NS];
+    const int64_t nfull = D >> 6; // full 64-column tiles
+    if (blockIdx.x == gridDim.x - 1) { // the extra workgroup: ragged tail only
+        if ((nfull << 6) < D) update_tail_columns<EMIT>(X, G, OUT, coef, c2h, n, D, nfull << 6, eps, lds);
+        return;
+    }
+
+    f32x4 *As4 = reinterpret_cast<f32x4 *>(lds);
+    float *cur = lds + NB * NB * 64 * 4 + wave * (kUpdCur + kUpdCarry);
+    float *carry = cur + kUpdCur;
+    // A operands for output block bi, steps 4sg..4sg+3, as one float4 per lane
+    for (int e = threadIdx.x; e < NB * NB * 64; e += 256) {
+        const int l = e & 63, sg = (e >> 6) % NB, bi = (e >> 6) / NB;
+        f32x4 v;
 #pragma unroll
-    for (int bi = 0; bi < NB; ++bi)
-#pragma unroll
-        for (int s = 0; s < NS; ++s) A[bi][s] = coef[kOffAT + (bi * NS + s) * kWave + lane];
+        for (int k = 0; k < 4; ++k) v[k] = coef[kOffAT + (bi * NS + 4 * sg + k) * kWave + l];
+        As4[e] = v;
+    }
     float rho[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         const int row = 16 * (s >> 2) + 4 * q + (s & 3);
-        rho[s] = (row < n) ? coef[kOffRho + row] : 0.f;
+        rho[s] = (FULLROWS || row < n) ? coef[kOffRho + row] : 0.f;
     }
+    __syncthreads();
 
-    const int64_t ntile = (D + 63) >> 6;
-    const int64_t nwaves = (int64_t)gridDim.x * 4;
-    for (int64_t tile = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); tile < ntile; tile += nwaves) {
-        const int64_t col = (tile << 6) + 4 * c16;
-        const bool full = ((tile << 6) + 64 <= D);
+    // this wave's contiguous range of tiles
+    const int64_t nwaves = (int64_t)(gridDim.x - 1) * 4;
+    const int64_t per = (nfull + nwaves - 1) / nwaves;
+    const int64_t w = (int64_t)blockIdx.x * 4 + wave;
+    const int64_t t0 = (w * per < nfull) ? w * per : nfull;
+    const int64_t t1 = (t0 + per < nfull) ? t0 + per : nfull;
+    const int64_t c_begin = t0 << 6;
+
+    // lane part of every load address: row 4q, column 4c; the rest is wave-uniform
+    const float *xlane = X + (int64_t)(4 * q) * D + 4 * c16;
+    const float *glane = G + (int64_t)(4 * q) * D + 4 * c16;
+    // stores: lane (rl = q, p = c16) writes row urow + q; a row's misalignment in floats is
+    // (a0 + row * dm) mod 32 because every tile starts at a multiple of 32 columns
+    float *olane = OUT + (int64_t)q * D + 4 * c16;
+    const uint32_t dm = (uint32_t)D & 31u;
+    const uint32_t a0 = (uint32_t)(reinterpret_cast<uintptr_t>(OUT) >> 2) & 31u;
+
+    for (int64_t tile = t0; tile < t1; ++tile) {
+        const int64_t base = tile << 6;
+        const float *xt = xlane + base, *gt = glane + base;
+        float *ot = olane + base;
+        int qv = q;
+        opaque(xt);
+        opaque(gt);
+        asm volatile("" : "+v"(ot), "+v"(qv)); // per-row store offsets are recomputed per tile
         f32x4 x[NS], z[NS];
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            const int row = 16 * (s >> 2) + 4 * q + (s & 3);
-            if (row < n) {
-                x[s] = load4(X + (int64_t)row * D, col, D, full);
-                z[s] = load4(G + (int64_t)row * D, col, D, full);
+            const int urow = 16 * (s >> 2) + (s & 3); // uniform part of the row index
+            if (FULLROWS || urow + 4 * q < n) {
+                x[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * D);
+                z[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * D);
             } else {
                 x[s] = f32x4{0.f, 0.f, 0.f, 0.f};
                 z[s] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -115,28 +200,80 @@ __global__ __launch_bounds__(256) void update_mfma_kernel(float *__restrict__ X,
         for (int s = 0; s < NS; ++s) z[s] -= c2h * x[s];
 
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            f32x4 acc[NB];
+        for (int bi = 0; bi < NB; ++bi) {
+            f32x4 acc[4];
 #pragma unroll
-            for (int bi = 0; bi < NB; ++bi) acc[bi] = f32x4{0.f, 0.f, 0.f, 0.f};
+            for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int s = 0; s < NS; ++s)
+            for (int sg = 0; sg < NB; ++sg) {
+                const f32x4 a4 = As4[(bi * NB + sg) * 64 + lane];
 #pragma unroll
-                for (int bi = 0; bi < NB; ++bi)
-                    acc[bi] = __builtin_amdgcn_mfma_f32_16x16x4f32(A[bi][s], z[s][t], acc[bi], 0, 0, 0);
+                for (int k = 0; k < 4; ++k)
 #pragma unroll
-            for (int bi = 0; bi < NB; ++bi)
+                    for (int t = 0; t < 4; ++t)
+                        acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[k], z[4 * sg + k][t], acc[t], 0, 0, 0);
+            }
+            // epilogue for rows 16bi + 4q + r, then stage the block row-major in LDS
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int s = 4 * bi + r;
-                    const float phi = fmaf(rho[s], x[s][t], acc[bi][r]);
-                    x[s][t] = EMIT ? phi : fmaf(eps, phi, x[s][t]);
+            for (int r = 0; r < 4; ++r) {
+                const int s = 4 * bi + r;
+                f32x4 o;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const float phi = fmaf(rho[s], x[s][t], acc[t][r]);
+                    o[t] = EMIT ? phi : fmaf(eps, phi, x[s][t]);
                 }
-        }
+                *reinterpret_cast<f32x4 *>(&cur[(4 * q + r) * 64 + 4 * c16]) = o;
+            }
+            // lanes exchange data through the wave-private LDS region: LDS operations of one wave
+            // execute in order, the fence only keeps the compiler from reordering them
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            // aligned stores: 4 instructions of 4 rows x 256 B; lane (rl = lane/16, p = lane%16)
 #pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const int row = 16 * (s >> 2) + 4 * q + (s & 3);
-            if (row < n) store4((EMIT ? PHI : X) + (int64_t)row * D, col, D, full, x[s]);
+            for (int k = 0; k < 4; ++k) {
+                const int urow = 16 * bi + 4 * k;    // uniform part of the row index
+                const int rloc = 4 * k + qv;         // row within the block (q plays rl here)
+                const int row = urow + qv;
+                const int ri = (int)((a0 + (uint32_t)row * dm) & 31u);
+                const int o0 = 4 * c16 - ri;         // window offset relative to the tile start
+                f32x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int o = o0 + e; // one address, so nothing is read outside the arrays
+                    v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : (rloc * 64 + o)];
+                }
+                if (FULLROWS || row < n) {
+                    float *dst = ot + (int64_t)urow * D - ri;
+                    if (tile != t0) {
+                        *reinterpret_cast<f32x4 *>(dst) = v;
+                    } else { // left end of the range: nothing left of c_begin is ours
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (o0 + e >= 0) dst[e] = v[e];
+                    }
+                }
+            }
+            // the block's last 32 columns become the carry of its 16 rows
+            {
+                const int rloc = lane >> 2, cc = 32 + 8 * (lane & 3);
+                const f32x4 v0 = *reinterpret_cast<const f32x4 *>(&cur[rloc * 64 + cc]);
+                const f32x4 v1 = *reinterpret_cast<const f32x4 *>(&cur[rloc * 64 + cc + 4]);
+                float *dstc = &carry[(16 * bi + rloc) * 32 + (cc - 32)];
+                *reinterpret_cast<f32x4 *>(dstc) = v0;
+                *reinterpret_cast<f32x4 *>(dstc + 4) = v1;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        }
+    }
+
+    // flush: the last r_i columns of the range are still in the carry
+    if (t1 > t0) {
+        const int64_t c_end = t1 << 6;
+        for (int idx = lane; idx < 16 * NB * 32; idx += 64) {
+            const int row = idx >> 5, cc = idx & 31;
+            const int ri = (int)((a0 + (uint32_t)row * dm) & 31u);
+            if (row < n && cc >= 32 - ri && c_end - 32 + cc >= c_begin)
+                OUT[(int64_t)row * D + c_end - 32 + cc] = carry[row * 32 + cc];
         }
     }
 }

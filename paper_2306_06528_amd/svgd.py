@@ -28,14 +28,18 @@ _lib.svgd_phi.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ct
                           ctypes.c_void_p, ctypes.c_void_p]
 _lib.svgd_get_last.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p, ctypes.c_void_p]
 _lib.svgd_destroy.argtypes = [_H]
+_lib.svgd_profile_begin.argtypes = [_H]
+_lib.svgd_profile_end.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
 _lib.svgd_last_device_error.argtypes = [_H]
 _lib.svgd_status_string.argtypes = [ctypes.c_int]
 _lib.svgd_status_string.restype = ctypes.c_char_p
 for _f in ("svgd_create", "svgd_set_bandwidth", "svgd_bandwidth", "svgd_step", "svgd_phi",
-           "svgd_get_last", "svgd_destroy", "svgd_last_device_error"):
+           "svgd_get_last", "svgd_destroy", "svgd_last_device_error", "svgd_profile_begin",
+           "svgd_profile_end"):
     getattr(_lib, _f).restype = ctypes.c_int
 
 SVGD_OK = 0
+KERNEL_KINDS = ("gram", "reduce", "bandwidth", "update")
 MAX_PARTICLES = 64
 
 
@@ -113,6 +117,16 @@ class Svgd:
         self._check(_lib.svgd_get_last(self._h, ctypes.byref(h), K.ctypes.data_as(ctypes.c_void_p),
                                        _stream_ptr(stream)))
         return h.value, K
+
+    def profile_begin(self):
+        self._check(_lib.svgd_profile_begin(self._h))
+
+    def profile_end(self):
+        """{kind: (total_ms, launches)} for the kernels launched since profile_begin()."""
+        ms = (ctypes.c_double * 4)()
+        cnt = (ctypes.c_int * 4)()
+        self._check(_lib.svgd_profile_end(self._h, ms, cnt))
+        return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_KINDS)}
 
     def close(self):
         if self._h:
