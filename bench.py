@@ -51,6 +51,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default 5: n=64, D=11,173,962)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the plain copy kernel once over G (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
@@ -69,6 +71,12 @@ def main():
     X = wl.X0.clone()
     G = wl.score(X, 0).clone()
     stream = torch.cuda.current_stream()
+
+    if args.calibrate_copy:
+        scratch = torch.empty_like(G)
+        svgd.diag_copy(scratch, G, stream=stream)
+        torch.cuda.synchronize()
+        del scratch
 
     with svgd.Svgd(n, D, 0) as eng:
         for _ in range(args.warmup):

@@ -109,6 +109,14 @@ enum svgd_kernel_kind {
 int svgd_profile_begin(svgd_handle_t h);
 int svgd_profile_end(svgd_handle_t h, double *ms_sum, int *count);
 
+/*
+ * Diagnostic: a plain device-to-device copy kernel of nbytes (a multiple of 16; dst and src
+ * DEVICE pointers, 16-byte aligned, not overlapping), enqueued on `stream`.  It reads and writes
+ * exactly nbytes, which makes it the yardstick for scaling hardware byte counters when the
+ * other kernels are profiled.
+ */
+int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream);
+
 /* Free the handle's scratch and invalidate the handle.  The caller synchronises beforehand. */
 int svgd_destroy(svgd_handle_t h);
 

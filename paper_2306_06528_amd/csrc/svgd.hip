@@ -215,7 +215,9 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
     } else {
         // workers walk contiguous ranges of full 64-column tiles; one more workgroup does D mod 64
         const int64_t nfull = D / 64;
-        const int grid = clampi((nfull + 3) / 4, 1, c->num_cu * 2) + 1;
+        // one worker workgroup per CU: the kernel overlaps its own loads with its multiplies, and
+        // fewer concurrent row streams keep more HBM pages open
+        const int grid = clampi((nfull + 3) / 4, 1, c->num_cu) + 1;
         const int NB = (n + 15) / 16;
 #define UPD(NBV, FULL) update_mfma_kernel<NBV, EMIT, FULL><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps)
         if (n == 32) UPD(2, true);
@@ -229,6 +231,14 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
     return SVGD_OK;
+}
+
+// Plain copy of known size: the yardstick against which hardware byte counters are scaled.
+__global__ __launch_bounds__(256) void diag_copy_kernel(const f32x4 *__restrict__ src,
+                                                        f32x4 *__restrict__ dst, int64_t n16)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256)
+        dst[i] = src[i];
 }
 
 } // namespace
@@ -368,6 +378,14 @@ int svgd_get_last(svgd_handle_t c, double *h_out, float *K_host, void *stream)
     if (e == hipSuccess) e = hipStreamSynchronize(s);
     if (e != hipSuccess) return fail(c, e);
     return SVGD_OK;
+}
+
+int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream)
+{
+    if (!dst || !src || nbytes < 16 || (nbytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
+        return SVGD_ERR_INVALID_ARG;
+    diag_copy_kernel<<<2048, 256, 0, (hipStream_t)stream>>>((const f32x4 *)src, (f32x4 *)dst, nbytes >> 4);
+    return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
 }
 
 int svgd_profile_begin(svgd_handle_t c)

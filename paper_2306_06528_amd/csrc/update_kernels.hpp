@@ -117,7 +117,8 @@ __device__ inline void update_tail_columns(float *__restrict__ X, const float *_
 }
 
 // keeps the compiler from turning per-row addresses into 2 x 16 loop-carried pointer pairs
-__device__ inline void opaque(const float *&p) { asm volatile("" : "+v"(p)); }
+// (an integer offset is laundered, not the pointer, so the accesses stay global_load/store)
+__device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 
 template <int NB, bool EMIT, bool FULLROWS>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -168,23 +169,21 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     const int64_t c_begin = t0 << 6;
 
     // lane part of every load address: row 4q, column 4c; the rest is wave-uniform
-    const float *xlane = X + (int64_t)(4 * q) * D + 4 * c16;
-    const float *glane = G + (int64_t)(4 * q) * D + 4 * c16;
+    const int64_t in_lane = (int64_t)(4 * q) * D + 4 * c16;
     // stores: lane (rl = q, p = c16) writes row urow + q; a row's misalignment in floats is
     // (a0 + row * dm) mod 32 because every tile starts at a multiple of 32 columns
-    float *olane = OUT + (int64_t)q * D + 4 * c16;
+    const int64_t out_lane = (int64_t)q * D + 4 * c16;
     const uint32_t dm = (uint32_t)D & 31u;
     const uint32_t a0 = (uint32_t)(reinterpret_cast<uintptr_t>(OUT) >> 2) & 31u;
 
-    for (int64_t tile = t0; tile < t1; ++tile) {
-        const int64_t base = tile << 6;
-        const float *xt = xlane + base, *gt = glane + base;
-        float *ot = olane + base;
-        int qv = q;
-        opaque(xt);
-        opaque(gt);
-        asm volatile("" : "+v"(ot), "+v"(qv)); // per-row store offsets are recomputed per tile
-        f32x4 x[NS], z[NS];
+    // Software pipeline: the loads of tile t+1 are issued while tile t is being multiplied, into
+    // registers as they fall free - x rows of block bi after that block's epilogue, g rows of
+    // step group sg after the last block has consumed them.
+    f32x4 x[NS], z[NS];
+    if (t0 < t1) {
+        int64_t in_off = in_lane + c_begin;
+        opaque(in_off);
+        const float *xt = X + in_off, *gt = G + in_off;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
             const int urow = 16 * (s >> 2) + (s & 3); // uniform part of the row index
@@ -196,6 +195,19 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 z[s] = f32x4{0.f, 0.f, 0.f, 0.f};
             }
         }
+    }
+
+    for (int64_t tile = t0; tile < t1; ++tile) {
+        const int64_t base = tile << 6;
+        const bool has_next = (tile + 1 < t1);
+        int64_t in_off = in_lane + base + 64; // next tile
+        int64_t out_off = out_lane + base;
+        int qv = q;
+        opaque(in_off);
+        opaque(out_off);
+        asm volatile("" : "+v"(qv)); // per-row store offsets are recomputed per tile
+        const float *xt = X + in_off, *gt = G + in_off;
+        float *ot = OUT + out_off;
 #pragma unroll
         for (int s = 0; s < NS; ++s) z[s] -= c2h * x[s];
 
@@ -212,6 +224,15 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
                         acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[k], z[4 * sg + k][t], acc[t], 0, 0, 0);
+                if (bi == NB - 1 && has_next) { // z rows 4sg..4sg+3 are dead: fetch the next tile's g
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int s = 4 * sg + k;
+                        const int urow = 16 * (s >> 2) + (s & 3);
+                        if (FULLROWS || urow + 4 * q < n)
+                            z[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * D);
+                    }
+                }
             }
             // epilogue for rows 16bi + 4q + r, then stage the block row-major in LDS
 #pragma unroll
@@ -224,6 +245,15 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                     o[t] = EMIT ? phi : fmaf(eps, phi, x[s][t]);
                 }
                 *reinterpret_cast<f32x4 *>(&cur[(4 * q + r) * 64 + 4 * c16]) = o;
+            }
+            if (has_next) { // x rows of this block are dead: fetch the next tile's
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int s = 4 * bi + r;
+                    const int urow = 16 * (s >> 2) + (s & 3);
+                    if (FULLROWS || urow + 4 * q < n)
+                        x[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * D);
+                }
             }
             // lanes exchange data through the wave-private LDS region: LDS operations of one wave
             // execute in order, the fence only keeps the compiler from reordering them

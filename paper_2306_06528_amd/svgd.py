@@ -28,6 +28,8 @@ _lib.svgd_phi.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ct
                           ctypes.c_void_p, ctypes.c_void_p]
 _lib.svgd_get_last.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p, ctypes.c_void_p]
 _lib.svgd_destroy.argtypes = [_H]
+_lib.svgd_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
+_lib.svgd_diag_copy.restype = ctypes.c_int
 _lib.svgd_profile_begin.argtypes = [_H]
 _lib.svgd_profile_end.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
 _lib.svgd_last_device_error.argtypes = [_H]
@@ -66,6 +68,16 @@ def _dev_matrix(t: torch.Tensor, name: str):
             and t.is_contiguous()):
         raise TypeError(f"{name} must be a contiguous 2-D float32 CUDA tensor")
     return t
+
+
+def diag_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):
+    """Plain copy kernel of known size (calibration of hardware byte counters)."""
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() != nbytes:
+        raise ValueError("dst and src must have the same size in bytes")
+    rc = _lib.svgd_diag_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream))
+    if rc != SVGD_OK:
+        raise SvgdError(rc)
 
 
 class Svgd:
