@@ -51,8 +51,8 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
                 d = S[tri(i, j, n)];
             } else {
                 d = S[tri(i, i, n)] + S[tri(j, j, n)] - 2.0 * S[tri(i, j, n)];
-                if (d < 0.0) d = 0.0;
             }
+            if (!(d > 0.0)) d = 0.0; // clamps rounding negatives (and -0.0)
             pr[pair_index(i, j, n)] = d;
         }
     }

@@ -51,10 +51,17 @@ __device__ inline f32x4 load4(const float *__restrict__ row, int64_t col, int64_
     return v;
 }
 
+// streaming variant for data that is read exactly once (G)
+__device__ inline f32x4 load4_stream(const float *__restrict__ row, int64_t col, int64_t D, bool full)
+{
+    if (full) return __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(row + col));
+    return load4(row, col, D, false);
+}
+
 __device__ inline void store4(float *__restrict__ row, int64_t col, int64_t D, bool full, f32x4 v)
 {
     if (full) {
-        *reinterpret_cast<f32x4u *>(row + col) = v;
+        __builtin_nontemporal_store(v, reinterpret_cast<f32x4u *>(row + col));
         return;
     }
     if (col + 0 < D) row[col + 0] = v.x;
@@ -63,11 +70,20 @@ __device__ inline void store4(float *__restrict__ row, int64_t col, int64_t D, b
     if (col + 3 < D) row[col + 3] = v.w;
 }
 
+// Sum over the 64 lanes of a wave, returned in every lane.  Four DPP adds give every lane the sum
+// of its row of 16 (quad swap, quad-pair swap, half-row mirror, row mirror); the four row sums are
+// then read from lanes 0, 16, 32, 48.  No LDS traffic, unlike shuffle-based reductions.
 __device__ inline float wave_sum(float v)
 {
-#pragma unroll
-    for (int m = 32; m >= 1; m >>= 1) v += __shfl_xor(v, m, kWave);
-    return v;
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, false));  // quad_perm [1,0,3,2]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, false));  // quad_perm [2,3,0,1]
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x141, 0xF, 0xF, false)); // row_half_mirror
+    v += __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x140, 0xF, 0xF, false)); // row_mirror
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+    return (r0 + r1) + (r2 + r3);
 }
 
 } // namespace svgd

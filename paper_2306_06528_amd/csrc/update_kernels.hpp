@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 #pragma unroll
         for (int j = 0; j < N; ++j) {
             x[j] = load4(X + (int64_t)j * D, col, D, full);
-            z[j] = load4(G + (int64_t)j * D, col, D, full);
+            z[j] = load4_stream(G + (int64_t)j * D, col, D, full);
         }
 #pragma unroll
         for (int j = 0; j < N; ++j) z[j] -= c2h * x[j];
