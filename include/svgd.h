@@ -49,8 +49,20 @@ enum svgd_status {
 #define SVGD_MAX_PARTICLES 64
 
 /*
+ * svgd_create flag.  The kernel matrix of step t+1 depends only on X after step t (paper App. B.2,
+ * closing remarks: a particle is updated only after the whole kernel matrix of the previous
+ * iterate exists).  With this flag svgd_step, while it still holds every updated column on chip,
+ * also accumulates the pairwise sums of the NEW X, and the next svgd_step on the same (X, n, D)
+ * skips its own pass over X.  The caller promises that between two svgd_step calls X is modified
+ * by nobody else; after touching X (or to be safe) call svgd_forget_carry.  svgd_bandwidth and
+ * svgd_phi always recompute from X and drop the carried sums.  Effective for n > 16 only; for
+ * smaller n the flag is accepted and ignored.
+ */
+#define SVGD_FLAG_CARRY_GRAM 1u
+
+/*
  * Create a handle for problems up to max_n particles (1..SVGD_MAX_PARTICLES) of up to max_D
- * parameters each on HIP device `device_id` (-1 = the current device).  `flags` must be 0.
+ * parameters each on HIP device `device_id` (-1 = the current device).  `flags` is 0 or SVGD_FLAG_CARRY_GRAM.
  * Allocates the handle's device scratch (about 20 MB).  On success *out receives the handle.
  */
 int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uint32_t flags);
@@ -61,6 +73,9 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
  * (the default).  Takes effect for subsequent calls.
  */
 int svgd_set_bandwidth(svgd_handle_t h, double h_fixed);
+
+/* Drop the pairwise sums carried from the last svgd_step (see SVGD_FLAG_CARRY_GRAM). */
+int svgd_forget_carry(svgd_handle_t h);
 
 /*
  * Compute d2, h, K and the row sums of K for X (device, n x D) and keep them in the handle

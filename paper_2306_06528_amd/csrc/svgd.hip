@@ -28,7 +28,14 @@ struct svgd_ctx {
     int max_n;
     int64_t max_D;
     int num_cu;
+    uint32_t flags;
     double h_fixed;
+    // Gram partials of the current X left behind by the last svgd_step (SVGD_FLAG_CARRY_GRAM)
+    bool carry_valid;
+    const float *carry_X;
+    int carry_n;
+    int64_t carry_D;
+    int carry_nparts;
     int last_n; // 0 = nothing computed yet
     int last_hip_error;
     float *partials;  // [kMaxParts][P]
@@ -155,11 +162,15 @@ void launch_update_valu(float *X, const float *G, float *PHI, const float *coef,
 int clampi(int64_t v, int lo, int hi) { return (int)(v < lo ? lo : (v > hi ? hi : v)); }
 
 // Passes 1 and 2: Gram partials -> fp64 reduction -> h, K, coefficient tables (all on `s`).
-int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t s)
+// With use_carry the partials the previous update left in c->partials stand in for pass 1.
+int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t s, bool use_carry)
 {
     const int P = n * (n + 1) / 2;
     int nparts, mode;
-    if (n <= 16) {
+    if (use_carry) {
+        nparts = c->carry_nparts;
+        mode = kModeGram;
+    } else if (n <= 16) {
         const int64_t ngroups = (D + 3) / 4;
         nparts = clampi((ngroups + 255) / 256, 1, c->num_cu * 4);
         mode = (n <= 8) ? kModeDiff : kModeGram;
@@ -200,8 +211,9 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
     return SVGD_OK;
 }
 
-// Pass 3.  EMIT = false: X updated in place; EMIT = true: phi written to PHI.
-template <bool EMIT>
+// Pass 3.  EMIT = false: X updated in place; EMIT = true: phi written to PHI.  CARRY (in-place,
+// n > 16 only): the update also leaves the Gram partials of the new X in c->partials.
+template <bool EMIT, bool CARRY>
 int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, float eps,
                hipStream_t s)
 {
@@ -217,9 +229,11 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int64_t nfull = D / 64;
         // one worker workgroup per CU: the kernel overlaps its own loads with its multiplies, and
         // fewer concurrent row streams keep more HBM pages open
-        const int grid = clampi((nfull + 3) / 4, 1, c->num_cu) + 1;
+        const int max_workers = c->num_cu < (kMaxParts - 1) / 4 ? c->num_cu : (kMaxParts - 1) / 4;
+        const int grid = clampi((nfull + 3) / 4, 1, max_workers) + 1;
         const int NB = (n + 15) / 16;
-#define UPD(NBV, FULL) update_mfma_kernel<NBV, EMIT, FULL><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps)
+        if (CARRY) c->carry_nparts = (grid - 1) * 4 + 1;
+#define UPD(NBV, FULL) update_mfma_kernel<NBV, EMIT, FULL, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps, c->partials)
         if (n == 32) UPD(2, true);
         else if (n == 48) UPD(3, true);
         else if (n == 64) UPD(4, true);
@@ -249,7 +263,8 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
 {
     if (!out) return SVGD_ERR_INVALID_ARG;
     *out = nullptr;
-    if (max_n < 1 || max_D < 1 || flags != 0 || device_id < -1) return SVGD_ERR_INVALID_ARG;
+    if (max_n < 1 || max_D < 1 || (flags & ~(uint32_t)SVGD_FLAG_CARRY_GRAM) != 0 || device_id < -1)
+        return SVGD_ERR_INVALID_ARG;
     if (max_n > SVGD_MAX_PARTICLES) return SVGD_ERR_TOO_LARGE;
 
     svgd_ctx *c = new (std::nothrow) svgd_ctx();
@@ -257,7 +272,13 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
     c->magic = 0;
     c->max_n = max_n;
     c->max_D = max_D;
+    c->flags = flags;
     c->h_fixed = 0.0;
+    c->carry_valid = false;
+    c->carry_X = nullptr;
+    c->carry_n = 0;
+    c->carry_D = 0;
+    c->carry_nparts = 0;
     c->last_n = 0;
     c->last_hip_error = 0;
     c->partials = nullptr;
@@ -314,6 +335,14 @@ int svgd_set_bandwidth(svgd_handle_t c, double h_fixed)
     return SVGD_OK;
 }
 
+int svgd_forget_carry(svgd_handle_t c)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    c->carry_valid = false;
+    return SVGD_OK;
+}
+
 int svgd_bandwidth(svgd_handle_t c, const float *X, int n, int64_t D, double *h_out_host, void *stream)
 {
     int rc = check_handle(c);
@@ -323,7 +352,8 @@ int svgd_bandwidth(svgd_handle_t c, const float *X, int n, int64_t D, double *h_
     if (rc) return rc;
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
-    rc = run_kernel_matrix(c, X, n, D, s);
+    c->carry_valid = false; // the partials buffer is about to be overwritten
+    rc = run_kernel_matrix(c, X, n, D, s, false);
     if (rc) return rc;
     if (h_out_host) {
         hipError_t e = hipMemcpyAsync(h_out_host, &c->state->h, sizeof(double), hipMemcpyDeviceToHost, s);
@@ -343,9 +373,19 @@ int svgd_step(svgd_handle_t c, float *X, const float *G, int n, int64_t D, float
     if (overlaps(X, G, n, D)) return SVGD_ERR_INVALID_ARG;
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
-    rc = run_kernel_matrix(c, X, n, D, s);
+    const bool carry_mode = (c->flags & SVGD_FLAG_CARRY_GRAM) && n > 16;
+    const bool use_carry = carry_mode && c->carry_valid && c->carry_X == X && c->carry_n == n && c->carry_D == D;
+    c->carry_valid = false;
+    rc = run_kernel_matrix(c, X, n, D, s, use_carry);
     if (rc) return rc;
-    return run_update<false>(c, X, G, nullptr, n, D, eps, s);
+    if (!carry_mode) return run_update<false, false>(c, X, G, nullptr, n, D, eps, s);
+    rc = run_update<false, true>(c, X, G, nullptr, n, D, eps, s);
+    if (rc) return rc;
+    c->carry_valid = true;
+    c->carry_X = X;
+    c->carry_n = n;
+    c->carry_D = D;
+    return SVGD_OK;
 }
 
 int svgd_phi(svgd_handle_t c, const float *X, const float *G, int n, int64_t D, float *PHI, void *stream)
@@ -358,9 +398,10 @@ int svgd_phi(svgd_handle_t c, const float *X, const float *G, int n, int64_t D, 
     if (overlaps(X, PHI, n, D) || overlaps(G, PHI, n, D)) return SVGD_ERR_INVALID_ARG;
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
-    rc = run_kernel_matrix(c, X, n, D, s);
+    c->carry_valid = false; // the partials buffer is about to be overwritten
+    rc = run_kernel_matrix(c, X, n, D, s, false);
     if (rc) return rc;
-    return run_update<true>(c, const_cast<float *>(X), G, PHI, n, D, 0.f, s);
+    return run_update<true, false>(c, const_cast<float *>(X), G, PHI, n, D, 0.f, s);
 }
 
 int svgd_get_last(svgd_handle_t c, double *h_out, float *K_host, void *stream)

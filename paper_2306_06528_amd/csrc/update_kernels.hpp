@@ -87,14 +87,14 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 constexpr int kUpdCur = 16 * 64;    // floats per wave
 constexpr int kUpdCarry = 64 * 32;  // floats per wave
 
-template <bool EMIT>
+template <bool EMIT, bool CARRY>
 __device__ inline void update_tail_columns(float *__restrict__ X, const float *__restrict__ G,
                                            float *__restrict__ OUT, const float *__restrict__ coef,
                                            float c2h, int n, int64_t D, int64_t col0, float eps,
-                                           float *__restrict__ lds)
+                                           float *__restrict__ lds, float *__restrict__ gram_out)
 {
     // plain per-column evaluation for the < 64 columns after the last full tile
-    float *zs = lds, *xs = lds + 64 * 64;
+    float *zs = lds, *xs = lds + 64 * 64, *yn = lds + 2 * 64 * 64;
     const int col = threadIdx.x & 63, part = threadIdx.x >> 6;
     const bool ok = (col0 + col < D);
     for (int j = part; j < n; j += 4) {
@@ -107,12 +107,32 @@ __device__ inline void update_tail_columns(float *__restrict__ X, const float *_
         zs[j * 64 + col] = gv - c2h * xv;
     }
     __syncthreads();
+    float m = 0.f;
+    if constexpr (CARRY) {
+        for (int j = 0; j < n; ++j) m += xs[j * 64 + col];
+        m *= 1.0f / (float)n;
+    }
     for (int i = part; i < n; i += 4) {
         float acc = 0.f;
         for (int j = 0; j < n; ++j) acc = fmaf(coef[kOffC + i * n + j], zs[j * 64 + col], acc);
         const float xv = xs[i * 64 + col];
         const float phi = fmaf(coef[kOffRho + i], xv, acc);
-        if (ok) OUT[(int64_t)i * D + col0 + col] = EMIT ? phi : fmaf(eps, phi, xv);
+        const float out = EMIT ? phi : fmaf(eps, phi, xv);
+        if (ok) OUT[(int64_t)i * D + col0 + col] = out;
+        if constexpr (CARRY) yn[i * 64 + col] = ok ? out - m : 0.f;
+    }
+    if constexpr (CARRY) {
+        // Gram of the updated, column-centred tail columns, in tri(i, j) order
+        __syncthreads();
+        const int P = n * (n + 1) / 2;
+        for (int p = threadIdx.x; p < P; p += 256) {
+            int i = 0, rem = p;
+            while (rem >= n - i) { rem -= n - i; ++i; }
+            const int j = i + rem;
+            float acc = 0.f;
+            for (int c = 0; c < 64; ++c) acc = fmaf(yn[i * 64 + c], yn[j * 64 + c], acc);
+            gram_out[p] = acc;
+        }
     }
 }
 
@@ -120,12 +140,17 @@ __device__ inline void update_tail_columns(float *__restrict__ X, const float *_
 // (an integer offset is laundered, not the pointer, so the accesses stay global_load/store)
 __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 
-template <int NB, bool EMIT, bool FULLROWS>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// CARRY: additionally accumulate the Gram of the UPDATED columns, centred by the pre-update column
+// mean (any per-column shift common to all particles leaves every d2 unchanged), and write one
+// partial per wave (+ one for the tail) to gram_out in the format of gram_mfma_kernel.  The next
+// step can then skip its own pass over X.
+template <int NB, bool EMIT, bool FULLROWS, bool CARRY>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CARRY ? 1 : 2, CARRY ? 1 : 2)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
                         const float *__restrict__ coef, const DevState *__restrict__ st, int n,
-                        int64_t D, float eps)
+                        int64_t D, float eps, float *__restrict__ gram_out)
 {
+    static_assert(!(CARRY && EMIT), "the Gram is carried only when X is updated");
     constexpr int NS = 4 * NB; // contraction steps = rows per lane
     // [A operands: NB*NB*64 float4][4 waves x (cur + carry)]
     __shared__ __attribute__((aligned(16))) float lds[NB * NB * 64 * 4 + 4 * (kUpdCur + kUpdCarry)];
@@ -137,9 +162,30 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
 
     const int64_t nfull = D >> 6; // full 64-column tiles
     if (blockIdx.x == gridDim.x - 1) { // the extra workgroup: ragged tail only
-        if ((nfull << 6) < D) update_tail_columns<EMIT>(X, G, OUT, coef, c2h, n, D, nfull << 6, eps, lds);
+        float *tail_out = nullptr;
+        if constexpr (CARRY) {
+            const int P = n * (n + 1) / 2;
+            tail_out = gram_out + (int64_t)(gridDim.x - 1) * 4 * P; // after the worker waves' partials
+            if ((nfull << 6) >= D)
+                for (int p = threadIdx.x; p < P; p += 256) tail_out[p] = 0.f;
+        }
+        if ((nfull << 6) < D)
+            update_tail_columns<EMIT, CARRY>(X, G, OUT, coef, c2h, n, D, nfull << 6, eps, lds, tail_out);
         return;
     }
+
+    // With CARRY the staging block doubles as the Gram operand source (lane = row reads), so its
+    // 16-byte granules are XOR-swizzled by the row; without it the block is plain row-major.
+    auto cur_index = [](int rloc, int col) {
+        return CARRY ? rloc * 64 + ((((col >> 2) ^ rloc) & 15) << 2) + (col & 3) : rloc * 64 + col;
+    };
+    constexpr int NPAIR = NB * (NB + 1) / 2;
+    f32x4 accg[CARRY ? NPAIR : 1];
+    if constexpr (CARRY) {
+#pragma unroll
+        for (int p = 0; p < NPAIR; ++p) accg[p] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    const float inv_n = 1.0f / (float)n;
 
     f32x4 *As4 = reinterpret_cast<f32x4 *>(lds);
     float *cur = lds + NB * NB * 64 * 4 + wave * (kUpdCur + kUpdCarry);
@@ -208,6 +254,27 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         asm volatile("" : "+v"(qv)); // per-row store offsets are recomputed per tile
         const float *xt = X + in_off, *gt = G + in_off;
         float *ot = OUT + out_off;
+        f32x4 mg[CARRY ? 4 : 1];      // pre-update column means in the Gram operand layout
+        f32x4 ag[CARRY ? NB : 1][4];  // Gram operands of the blocks finished so far
+        if constexpr (CARRY) {
+            f32x4 m = x[0];
+#pragma unroll
+            for (int s = 1; s < NS; ++s) m += x[s];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                float v = m[e];
+                v += __shfl_xor(v, 16, kWave);
+                v += __shfl_xor(v, 32, kWave);
+                m[e] = v * inv_n;
+            }
+            // through the (currently idle) staging block: lane (q, c) knows columns 4c..4c+3,
+            // the Gram layout wants columns 4(4st + q)..+3
+            if (q == 0) *reinterpret_cast<f32x4 *>(&cur[4 * c16]) = m;
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+            for (int st4 = 0; st4 < 4; ++st4) mg[st4] = *reinterpret_cast<const f32x4 *>(&cur[4 * (4 * st4 + q)]);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        }
 #pragma unroll
         for (int s = 0; s < NS; ++s) z[s] -= c2h * x[s];
 
@@ -244,7 +311,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                     const float phi = fmaf(rho[s], x[s][t], acc[t][r]);
                     o[t] = EMIT ? phi : fmaf(eps, phi, x[s][t]);
                 }
-                *reinterpret_cast<f32x4 *>(&cur[(4 * q + r) * 64 + 4 * c16]) = o;
+                *reinterpret_cast<f32x4 *>(&cur[cur_index(4 * q + r, 4 * c16)]) = o;
             }
             if (has_next) { // x rows of this block are dead: fetch the next tile's
 #pragma unroll
@@ -270,7 +337,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const int o = o0 + e; // one address, so nothing is read outside the arrays
-                    v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : (rloc * 64 + o)];
+                    v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : cur_index(rloc, o)];
                 }
                 if (FULLROWS || row < n) {
                     float *dst = ot + (int64_t)urow * D - ri;
@@ -286,11 +353,26 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             // the block's last 32 columns become the carry of its 16 rows
             {
                 const int rloc = lane >> 2, cc = 32 + 8 * (lane & 3);
-                const f32x4 v0 = *reinterpret_cast<const f32x4 *>(&cur[rloc * 64 + cc]);
-                const f32x4 v1 = *reinterpret_cast<const f32x4 *>(&cur[rloc * 64 + cc + 4]);
+                const f32x4 v0 = *reinterpret_cast<const f32x4 *>(&cur[cur_index(rloc, cc)]);
+                const f32x4 v1 = *reinterpret_cast<const f32x4 *>(&cur[cur_index(rloc, cc + 4)]);
                 float *dstc = &carry[(16 * bi + rloc) * 32 + (cc - 32)];
                 *reinterpret_cast<f32x4 *>(dstc) = v0;
                 *reinterpret_cast<f32x4 *>(dstc + 4) = v1;
+            }
+            if constexpr (CARRY) {
+                // lane (q, rr = c16) takes row rr of this block, columns 4(4st + q)..+3, centred
+#pragma unroll
+                for (int st4 = 0; st4 < 4; ++st4)
+                    ag[bi][st4] = *reinterpret_cast<const f32x4 *>(&cur[cur_index(c16, 4 * (4 * st4 + q))]) - mg[st4];
+#pragma unroll
+                for (int b = 0; b <= bi; ++b) {
+                    const int pidx = b * NB - (b * (b - 1)) / 2 + (bi - b); // pair (b, bi), b <= bi
+#pragma unroll
+                    for (int st4 = 0; st4 < 4; ++st4)
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            accg[pidx] = __builtin_amdgcn_mfma_f32_16x16x4f32(ag[b][st4][e], ag[bi][st4][e], accg[pidx], 0, 0, 0);
+                }
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
@@ -304,6 +386,26 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             const int ri = (int)((a0 + (uint32_t)row * dm) & 31u);
             if (row < n && cc >= 32 - ri && c_end - 32 + cc >= c_begin)
                 OUT[(int64_t)row * D + c_end - 32 + cc] = carry[row * 32 + cc];
+        }
+    }
+
+    if constexpr (CARRY) {
+        // one partial per wave, upper triangle in tri(i, j) order (zeros if the range was empty)
+        const int P = n * (n + 1) / 2;
+        float *out = gram_out + w * P;
+        int p = 0;
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+#pragma unroll
+            for (int b2 = b; b2 < NB; ++b2) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int i = 16 * b + 4 * q + r;
+                    const int j = 16 * b2 + c16;
+                    if (i <= j && j < n) out[tri(i, j, n)] = accg[p][r];
+                }
+                ++p;
+            }
         }
     }
 }

@@ -20,6 +20,8 @@ _lib = ctypes.CDLL(LIB_PATH)
 _H = ctypes.c_void_p
 _lib.svgd_create.argtypes = [ctypes.POINTER(_H), ctypes.c_int, ctypes.c_int64, ctypes.c_int, ctypes.c_uint32]
 _lib.svgd_set_bandwidth.argtypes = [_H, ctypes.c_double]
+_lib.svgd_forget_carry.argtypes = [_H]
+_lib.svgd_forget_carry.restype = ctypes.c_int
 _lib.svgd_bandwidth.argtypes = [_H, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
                                 ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
 _lib.svgd_step.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
@@ -41,6 +43,7 @@ for _f in ("svgd_create", "svgd_set_bandwidth", "svgd_bandwidth", "svgd_step", "
     getattr(_lib, _f).restype = ctypes.c_int
 
 SVGD_OK = 0
+FLAG_CARRY_GRAM = 1
 KERNEL_KINDS = ("gram", "reduce", "bandwidth", "update")
 MAX_PARTICLES = 64
 
@@ -83,9 +86,9 @@ def diag_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):
 class Svgd:
     """Handle of the library: svgd_create on construction, svgd_destroy on close()."""
 
-    def __init__(self, max_n: int, max_D: int, device: int = -1):
+    def __init__(self, max_n: int, max_D: int, device: int = -1, flags: int = 0):
         self._h = _H()
-        rc = _lib.svgd_create(ctypes.byref(self._h), int(max_n), int(max_D), int(device), 0)
+        rc = _lib.svgd_create(ctypes.byref(self._h), int(max_n), int(max_D), int(device), int(flags))
         if rc != SVGD_OK:
             self._h = _H()
             raise SvgdError(rc)
@@ -96,6 +99,9 @@ class Svgd:
 
     def set_bandwidth(self, h_fixed: float):
         self._check(_lib.svgd_set_bandwidth(self._h, float(h_fixed)))
+
+    def forget_carry(self):
+        self._check(_lib.svgd_forget_carry(self._h))
 
     def bandwidth(self, X, want_h=True, stream=None):
         X = _dev_matrix(X, "X")

@@ -288,3 +288,77 @@ def test_config4_resnet18_full_size(svgd):
 
 def test_config5_large_ensemble_full_size(svgd):
     _full_size_check(svgd, 5)
+
+
+# ----------------------------------------------------------------------------------------------
+# carried Gram (SVGD_FLAG_CARRY_GRAM): step t's update also accumulates the pair sums of the new
+# X, and step t+1 skips its own pass over X
+# ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,D", [(64, 70_001), (32, 4096), (17, 1531), (48, 129), (33, 200_000), (64, 63)])
+def test_carried_gram_matches_oracle_every_step(svgd, n, D):
+    X, G = _random_problem(n, D, 31 * n + D, x_std=0.3)
+    eps = 0.05
+    with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM) as eng:
+        for step in range(4):
+            Xh = X.cpu().numpy()
+            eng.step(X, G, eps)           # steps 1.. use the sums carried from the previous step
+            h, K = eng.get_last(n)
+            ref = orc.step(Xh, G.cpu().numpy(), eps)
+            assert abs(h - ref["h"]) / ref["h"] <= TOL_H, f"step {step}: h {h} vs {ref['h']}"
+            assert np.abs(K - ref["K"]).max() <= TOL_K, f"step {step}"
+            err = np.abs(X.cpu().numpy() - ref["X_new"]).max() / np.abs(ref["X_new"]).max()
+            assert err <= 1e-6, f"step {step}: X err {err:.3e}"
+
+
+def test_carried_gram_is_dropped_when_it_must_be(svgd):
+    n, D = 32, 10_007
+    X, G = _random_problem(n, D, 77)
+    with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM) as eng:
+        eng.step(X, G, 0.01)
+        # the caller changes X behind the library's back and says so
+        X.mul_(1.5)
+        eng.forget_carry()
+        Xh = X.cpu().numpy()
+        eng.step(X, G, 0.01)
+        h, _ = eng.get_last(n)
+        assert abs(h - orc.step(Xh, G.cpu().numpy(), 0.01, want_phi=False, want_xnew=False)["h"]) / h <= TOL_H
+        # a different buffer of the same shape is not mistaken for the carried one
+        X2 = (X * 0.5).contiguous()
+        X2h = X2.cpu().numpy()
+        eng.step(X2, G, 0.01)
+        h2, _ = eng.get_last(n)
+        assert abs(h2 - orc.step(X2h, G.cpu().numpy(), 0.01, want_phi=False, want_xnew=False)["h"]) / h2 <= TOL_H
+        # svgd_phi / svgd_bandwidth recompute from X and leave a consistent state behind
+        PHI = torch.empty_like(X2)
+        X2h = X2.cpu().numpy()
+        eng.phi(X2, G, PHI)
+        eng.step(X2, G, 0.01)
+        h3, _ = eng.get_last(n)
+        assert abs(h3 - orc.step(X2h, G.cpu().numpy(), 0.01, want_phi=False, want_xnew=False)["h"]) / h3 <= TOL_H
+
+
+def test_config5_carried_gram_full_size(svgd):
+    """Config 5 at full size with the carried Gram: h and K of the second step against the oracle."""
+    wl = workloads.make(5, device="cuda")
+    n, D = wl.n, wl.D
+    X = wl.X0.clone()
+    G = wl.score(X, 0)
+    with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM) as eng:
+        eng.step(X, G, wl.cfg.eps)
+        X1 = X.cpu().numpy()
+        eng.step(X, G, wl.cfg.eps)
+        h, K = eng.get_last(n)
+        torch.cuda.synchronize()
+    d2 = orc.pairwise_d2(X1)
+    h_ref = orc.bandwidth(d2)
+    K_ref, _ = orc.kernel(d2, h_ref)
+    assert abs(h - h_ref) / h_ref <= TOL_H
+    assert np.abs(K - K_ref).max() <= TOL_K
+    rng = np.random.default_rng(5)
+    Gh = G.cpu().numpy()
+    X2 = X.cpu().numpy()
+    for s in [0, D - 4096] + [int(v) for v in rng.integers(0, D - 4096, 3)]:
+        phi = orc.phi_cols(X1, Gh, K_ref, h_ref, s, 4096)
+        want = X1[:, s:s + 4096].astype(np.float64) + wl.cfg.eps * phi
+        err = np.abs(X2[:, s:s + 4096] - want).max() / np.abs(want).max()
+        assert err <= 1e-6
