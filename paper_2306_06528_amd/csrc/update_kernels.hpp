@@ -11,6 +11,8 @@
 // column's inputs, and every thread/wave loads all n rows of its columns before storing any, so
 // every phi_i is computed from the pre-step X.
 #pragma once
+#include <type_traits>
+
 #include "common.hpp"
 
 namespace svgd {
@@ -144,14 +146,24 @@ __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 // mean (any per-column shift common to all particles leaves every d2 unchanged), and write one
 // partial per wave (+ one for the tail) to gram_out in the format of gram_mfma_kernel.  The next
 // step can then skip its own pass over X.
+//
+// Instruction mix.  One wave per SIMD has to keep the matrix pipe, the vector ALU, LDS and the
+// memory pipe busy at once, so the work of a tile is ordered as
+//     M(0) | M(1)+E(0)+G(0) | M(2)+E(1)+G(1) | ... | E(NB-1)+G(NB-1)
+// with M(b) = the MFMAs and epilogue of output block b, E(b) = the aligned stores of block b
+// (LDS reads, address arithmetic, global stores) and G(b) = the Gram MFMAs of block b (CARRY).
+// The pieces of one group are written interleaved and sit in one basic block (no branches in the
+// steady-state tile), which lets the scheduler fill the MFMA shadows.  The first tile of a range,
+// which has to mask its left edge, is a separate, branchy instance of the same code.
 template <int NB, bool EMIT, bool FULLROWS, bool CARRY>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(CARRY ? 1 : 2, CARRY ? 1 : 2)))
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
                         const float *__restrict__ coef, const DevState *__restrict__ st, int n,
                         int64_t D, float eps, float *__restrict__ gram_out)
 {
     static_assert(!(CARRY && EMIT), "the Gram is carried only when X is updated");
     constexpr int NS = 4 * NB; // contraction steps = rows per lane
+    constexpr int NPAIR = NB * (NB + 1) / 2;
     // [A operands: NB*NB*64 float4][4 waves x (cur + carry)]
     __shared__ __attribute__((aligned(16))) float lds[NB * NB * 64 * 4 + 4 * (kUpdCur + kUpdCarry)];
     const int lane = threadIdx.x & 63;
@@ -179,7 +191,6 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     auto cur_index = [](int rloc, int col) {
         return CARRY ? rloc * 64 + ((((col >> 2) ^ rloc) & 15) << 2) + (col & 3) : rloc * 64 + col;
     };
-    constexpr int NPAIR = NB * (NB + 1) / 2;
     f32x4 accg[CARRY ? NPAIR : 1];
     if constexpr (CARRY) {
 #pragma unroll
@@ -222,38 +233,43 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     const uint32_t dm = (uint32_t)D & 31u;
     const uint32_t a0 = (uint32_t)(reinterpret_cast<uintptr_t>(OUT) >> 2) & 31u;
 
-    // Software pipeline: the loads of tile t+1 are issued while tile t is being multiplied, into
-    // registers as they fall free - x rows of block bi after that block's epilogue, g rows of
-    // step group sg after the last block has consumed them.
+    // Software pipeline across tiles: the loads of tile t+1 are issued while tile t is being
+    // multiplied, into registers as they fall free - x rows of block bi after that block's
+    // epilogue, g rows of step group sg after the last block has consumed them.  The last tile of
+    // the range "prefetches" itself again (a few KB that nobody uses) so that the steady-state
+    // code has no branch.
     f32x4 x[NS], z[NS];
+    auto load_x = [&](const float *xt, int s) __attribute__((always_inline)) {
+        const int urow = 16 * (s >> 2) + (s & 3); // uniform part of the row index
+        if (FULLROWS || urow + 4 * q < n) x[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * D);
+    };
+    auto load_g = [&](const float *gt, int s) __attribute__((always_inline)) {
+        const int urow = 16 * (s >> 2) + (s & 3);
+        if (FULLROWS || urow + 4 * q < n) z[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * D);
+    };
     if (t0 < t1) {
         int64_t in_off = in_lane + c_begin;
         opaque(in_off);
-        const float *xt = X + in_off, *gt = G + in_off;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            const int urow = 16 * (s >> 2) + (s & 3); // uniform part of the row index
-            if (FULLROWS || urow + 4 * q < n) {
-                x[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * D);
-                z[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * D);
-            } else {
-                x[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-                z[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
+            x[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            z[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            load_x(X + in_off, s);
+            load_g(G + in_off, s);
         }
     }
 
-    for (int64_t tile = t0; tile < t1; ++tile) {
+    auto process_tile = [&](auto first_tag, int64_t tile) __attribute__((always_inline)) {
+        constexpr bool FIRST = decltype(first_tag)::value;
         const int64_t base = tile << 6;
-        const bool has_next = (tile + 1 < t1);
-        int64_t in_off = in_lane + base + 64; // next tile
+        const int64_t next = (tile + 1 < t1) ? tile + 1 : tile;
+        int64_t in_off = in_lane + (next << 6);
         int64_t out_off = out_lane + base;
-        int qv = q;
+        const int qv = q; // (the per-row store offsets are tile-invariant and may be hoisted)
         opaque(in_off);
-        opaque(out_off);
-        asm volatile("" : "+v"(qv)); // per-row store offsets are recomputed per tile
         const float *xt = X + in_off, *gt = G + in_off;
         float *ot = OUT + out_off;
+
         f32x4 mg[CARRY ? 4 : 1];      // pre-update column means in the Gram operand layout
         f32x4 ag[CARRY ? NB : 1][4];  // Gram operands of the blocks finished so far
         if constexpr (CARRY) {
@@ -270,16 +286,58 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             // through the (currently idle) staging block: lane (q, c) knows columns 4c..4c+3,
             // the Gram layout wants columns 4(4st + q)..+3
             if (q == 0) *reinterpret_cast<f32x4 *>(&cur[4 * c16]) = m;
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
 #pragma unroll
             for (int st4 = 0; st4 < 4; ++st4) mg[st4] = *reinterpret_cast<const f32x4 *>(&cur[4 * (4 * st4 + q)]);
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
 #pragma unroll
         for (int s = 0; s < NS; ++s) z[s] -= c2h * x[s];
 
+        // E(b), one of its four store groups: 4 rows x 256 B, lane (rl = q, p = c16)
+        auto emit_group = [&](int b, int k) __attribute__((always_inline)) {
+            const int urow = 16 * b + 4 * k;     // uniform part of the row index
+            const int rloc = 4 * k + qv;         // row within the block
+            const int row = urow + qv;
+            const int ri = (int)((a0 + (uint32_t)row * dm) & 31u);
+            const int o0 = 4 * c16 - ri;         // window offset relative to the tile start
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int o = o0 + e; // one address, so nothing is read outside the arrays
+                v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : cur_index(rloc, o)];
+            }
+            if (FULLROWS || row < n) {
+                float *dst = ot + (int64_t)urow * D - ri;
+                if constexpr (!FIRST) {
+                    *reinterpret_cast<f32x4 *>(dst) = v;
+                } else { // left end of the range: nothing left of c_begin is ours
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        if (o0 + e >= 0) dst[e] = v[e];
+                }
+            }
+        };
+        // after E(b): the block's last 32 columns become the carry of its 16 rows
+        auto carry_copy = [&](int b) __attribute__((always_inline)) {
+            const int rloc = lane >> 2, cc = 32 + 8 * (lane & 3);
+            const f32x4 v0 = *reinterpret_cast<const f32x4 *>(&cur[cur_index(rloc, cc)]);
+            const f32x4 v1 = *reinterpret_cast<const f32x4 *>(&cur[cur_index(rloc, cc + 4)]);
+            float *dstc = &carry[(16 * b + rloc) * 32 + (cc - 32)];
+            *reinterpret_cast<f32x4 *>(dstc) = v0;
+            *reinterpret_cast<f32x4 *>(dstc + 4) = v1;
+        };
+        // G(b), the part that pairs block b with block b0 <= b
+        auto gram_pair = [&](int b0, int b) __attribute__((always_inline)) {
+            const int pidx = b0 * NB - (b0 * (b0 - 1)) / 2 + (b - b0);
+#pragma unroll
+            for (int st4 = 0; st4 < 4; ++st4)
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    accg[pidx] = __builtin_amdgcn_mfma_f32_16x16x4f32(ag[b0][st4][e], ag[b][st4][e], accg[pidx], 0, 0, 0);
+        };
+
 #pragma unroll
         for (int bi = 0; bi < NB; ++bi) {
+            // M(bi), interleaved with E(bi-1) and G(bi-1)
             f32x4 acc[4];
 #pragma unroll
             for (int t = 0; t < 4; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -291,17 +349,22 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
                         acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[k], z[4 * sg + k][t], acc[t], 0, 0, 0);
-                if (bi == NB - 1 && has_next) { // z rows 4sg..4sg+3 are dead: fetch the next tile's g
+                if (bi == NB - 1) { // z rows 4sg..4sg+3 are dead: fetch the next tile's g
 #pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const int s = 4 * sg + k;
-                        const int urow = 16 * (s >> 2) + (s & 3);
-                        if (FULLROWS || urow + 4 * q < n)
-                            z[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * D);
+                    for (int k = 0; k < 4; ++k) load_g(gt, 4 * sg + k);
+                }
+                if (bi > 0) {
+                    // the four store groups of the previous block are spread over the NB step groups
+#pragma unroll
+                    for (int k = 0; k < 4; ++k)
+                        if (k * NB / 4 == sg) emit_group(bi - 1, k);
+                    if constexpr (CARRY) {
+                        if (sg < bi) gram_pair(sg, bi - 1); // pairs (0..bi-1, bi-1): one per step group
                     }
                 }
             }
-            // epilogue for rows 16bi + 4q + r, then stage the block row-major in LDS
+            if (bi > 0) carry_copy(bi - 1);
+            // epilogue for rows 16bi + 4q + r, then stage the block in LDS
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int s = 4 * bi + r;
@@ -313,69 +376,32 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 }
                 *reinterpret_cast<f32x4 *>(&cur[cur_index(4 * q + r, 4 * c16)]) = o;
             }
-            if (has_next) { // x rows of this block are dead: fetch the next tile's
+            // x rows of this block are dead: fetch the next tile's
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int s = 4 * bi + r;
-                    const int urow = 16 * (s >> 2) + (s & 3);
-                    if (FULLROWS || urow + 4 * q < n)
-                        x[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * D);
-                }
-            }
-            // lanes exchange data through the wave-private LDS region: LDS operations of one wave
-            // execute in order, the fence only keeps the compiler from reordering them
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-            // aligned stores: 4 instructions of 4 rows x 256 B; lane (rl = lane/16, p = lane%16)
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                const int urow = 16 * bi + 4 * k;    // uniform part of the row index
-                const int rloc = 4 * k + qv;         // row within the block (q plays rl here)
-                const int row = urow + qv;
-                const int ri = (int)((a0 + (uint32_t)row * dm) & 31u);
-                const int o0 = 4 * c16 - ri;         // window offset relative to the tile start
-                f32x4 v;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int o = o0 + e; // one address, so nothing is read outside the arrays
-                    v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : cur_index(rloc, o)];
-                }
-                if (FULLROWS || row < n) {
-                    float *dst = ot + (int64_t)urow * D - ri;
-                    if (tile != t0) {
-                        *reinterpret_cast<f32x4 *>(dst) = v;
-                    } else { // left end of the range: nothing left of c_begin is ours
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (o0 + e >= 0) dst[e] = v[e];
-                    }
-                }
-            }
-            // the block's last 32 columns become the carry of its 16 rows
-            {
-                const int rloc = lane >> 2, cc = 32 + 8 * (lane & 3);
-                const f32x4 v0 = *reinterpret_cast<const f32x4 *>(&cur[cur_index(rloc, cc)]);
-                const f32x4 v1 = *reinterpret_cast<const f32x4 *>(&cur[cur_index(rloc, cc + 4)]);
-                float *dstc = &carry[(16 * bi + rloc) * 32 + (cc - 32)];
-                *reinterpret_cast<f32x4 *>(dstc) = v0;
-                *reinterpret_cast<f32x4 *>(dstc + 4) = v1;
-            }
+            for (int r = 0; r < 4; ++r) load_x(xt, 4 * bi + r);
             if constexpr (CARRY) {
                 // lane (q, rr = c16) takes row rr of this block, columns 4(4st + q)..+3, centred
 #pragma unroll
                 for (int st4 = 0; st4 < 4; ++st4)
                     ag[bi][st4] = *reinterpret_cast<const f32x4 *>(&cur[cur_index(c16, 4 * (4 * st4 + q))]) - mg[st4];
-#pragma unroll
-                for (int b = 0; b <= bi; ++b) {
-                    const int pidx = b * NB - (b * (b - 1)) / 2 + (bi - b); // pair (b, bi), b <= bi
-#pragma unroll
-                    for (int st4 = 0; st4 < 4; ++st4)
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            accg[pidx] = __builtin_amdgcn_mfma_f32_16x16x4f32(ag[b][st4][e], ag[bi][st4][e], accg[pidx], 0, 0, 0);
-                }
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         }
+        // E(NB-1) interleaved with G(NB-1)
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            emit_group(NB - 1, k);
+            if constexpr (CARRY) {
+#pragma unroll
+                for (int b0 = 0; b0 < NB; ++b0)
+                    if (b0 * 4 / NB == k) gram_pair(b0, NB - 1);
+            }
+        }
+        carry_copy(NB - 1);
+    };
+
+    if (t0 < t1) {
+        process_tile(std::true_type{}, t0);
+        for (int64_t tile = t0 + 1; tile < t1; ++tile) process_tile(std::false_type{}, tile);
     }
 
     // flush: the last r_i columns of the range are still in the carry
