@@ -308,7 +308,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             if (FULLROWS || row < n) {
                 float *dst = ot + (int64_t)urow * D - ri;
                 if constexpr (!FIRST) {
-                    *reinterpret_cast<f32x4 *>(dst) = v;
+                    __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(dst));
                 } else { // left end of the range: nothing left of c_begin is ours
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
