@@ -18,6 +18,27 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+
+# HBM traffic of the dominant kernel from rocprofv3 --pmc (see profiles/): average KiB per launch
+# as FETCH_SIZE / WRITE_SIZE report it, and the factors that the same counters need to reproduce
+# the known size of the plain copy kernel (svgd_diag_copy).  The numbers belong to one version of
+# the kernel source: if the hash below no longer matches, "traffic" is reported as null.
+TRAFFIC_COUNTERS = {
+    # (config, carried Gram?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
+    (5, True): (4081915.6, 2803354.8),
+}
+TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
+TRAFFIC_SOURCE_SHA256 = "6440bbe400d155b62ef4d92ca10eb2b58ab8487427c32c0bc10559d044679988"
+
+
+def kernel_source_hash():
+    import hashlib
+    d = os.path.join(ROOT, "paper_2306_06528_amd", "csrc")
+    h = hashlib.sha256()
+    for name in ("update_kernels.hpp", "common.hpp"):
+        with open(os.path.join(d, name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
 UPDATE_BYTES_PER_PARAM = 12    # read X, read G, write X
 STEP_BYTES_PER_PARAM = 16      # + the Gram pass reads X once more
 
@@ -107,6 +128,12 @@ def main():
     upd_gbs = UPDATE_BYTES_PER_PARAM * n * D / (upd_ms * 1e-3) / 1e9
     gram_gbs = 4 * n * D / (kern_ms["gram"] * 1e-3) / 1e9 if kern_ms["gram"] > 0 else None
 
+    traffic = None
+    key = (args.config, carry)
+    if key in TRAFFIC_COUNTERS and kernel_source_hash() == TRAFFIC_SOURCE_SHA256:
+        f_kib, w_kib = TRAFFIC_COUNTERS[key]
+        traffic = (f_kib * TRAFFIC_SCALE[0] + w_kib * TRAFFIC_SCALE[1]) * 1024.0
+
     out = {
         "metric": "SVGD particle-params updated/s",
         "value": value,
@@ -128,13 +155,14 @@ def main():
         "kernel_ms": kern_ms,
         "gram_gbs": gram_gbs,
         "roofline": {
-            "kernel": "update (fused K.[G|X] in-place update)",
+            "kernel": "update_mfma_kernel (fused K.[G|X] in-place update" +
+                      (", also accumulating the next step's pair sums)" if carry else ")"),
             "bound": "hbm",
             "achieved": upd_gbs,
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": upd_gbs / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": traffic,
         },
     }
     if not args.no_cpu_baseline:

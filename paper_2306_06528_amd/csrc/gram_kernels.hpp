@@ -98,14 +98,17 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
 //      lane (q, c), register r of pair (b, b') holds S[16b + 4q + r][16b' + c].
 // Any assignment of columns to k-slots is valid because every column is summed exactly once.
 // ---------------------------------------------------------------------------------------------
+constexpr int kGramWaves = 4; // waves per workgroup; adjacent 64-column slabs -> 1 KiB per row
+
 template <int NB>
-__global__ __launch_bounds__(128) void gram_mfma_kernel(const float *__restrict__ X, int n,
-                                                        int64_t D, float *__restrict__ partials)
+__global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float *__restrict__ X, int n,
+                                                                    int64_t D, float *__restrict__ partials)
 {
     constexpr int ROWS = 16 * NB;
     constexpr int RPL = 4 * NB; // rows per lane while loading
     constexpr int NPAIR = NB * (NB + 1) / 2;
-    __shared__ float lds[2][ROWS * 64];
+    constexpr int TW = 64 * kGramWaves; // columns per workgroup tile
+    __shared__ float lds[kGramWaves][ROWS * 64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = lane >> 4, c16 = lane & 15;
@@ -116,10 +119,10 @@ __global__ __launch_bounds__(128) void gram_mfma_kernel(const float *__restrict_
 #pragma unroll
     for (int p = 0; p < NPAIR; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int64_t ntile = (D + 127) >> 7;
+    const int64_t ntile = (D + TW - 1) / TW;
     f32x4 x[RPL];
     auto load_slab = [&](int64_t tile) {
-        const int64_t wcol = (tile << 7) + (wave << 6);
+        const int64_t wcol = tile * TW + (wave << 6);
         const int64_t col = wcol + 4 * c16;
         const bool full = (wcol + 64 <= D);
 #pragma unroll
@@ -140,14 +143,14 @@ __global__ __launch_bounds__(128) void gram_mfma_kernel(const float *__restrict_
             v += __shfl_xor(v, 32, kWave);
             s[c] = v * inv_n;
         }
-        __syncthreads(); // the previous slab has been consumed
+        // The LDS region is private to this wave and a wave's LDS operations execute in order, so
+        // no barrier is needed between consuming the previous slab and writing this one.
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int row = 4 * i + q;
             // rows >= n hold -mean here; they only reach entries with i or j >= n, never stored
             *reinterpret_cast<f32x4 *>(&my[row * 64 + ((c16 ^ (row & 15)) << 2)]) = x[i] - s;
         }
-        __syncthreads();
         // the next slab's loads are in flight while this one is multiplied
         if (tile + gridDim.x < ntile) load_slab(tile + gridDim.x);
 #pragma unroll
@@ -173,14 +176,14 @@ __global__ __launch_bounds__(128) void gram_mfma_kernel(const float *__restrict_
         }
     }
 
-    // combine the two waves through LDS, then store the upper triangle in tri(i, j) order
+    // combine the waves through LDS, then store the upper triangle in tri(i, j) order
     __syncthreads();
-    float *xch = &lds[0][0];
-    if (wave == 1) {
+    float *xch = &lds[0][0]; // [wave-1][pair][r][lane], NPAIR*256 floats per wave (<= ROWS*64)
+    if (wave > 0) {
 #pragma unroll
         for (int p = 0; p < NPAIR; ++p)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) xch[(p * 4 + r) * 64 + lane] = acc[p][r];
+            for (int r = 0; r < 4; ++r) xch[((wave - 1) * NPAIR * 4 + p * 4 + r) * 64 + lane] = acc[p][r];
     }
     __syncthreads();
     if (wave == 0) {
@@ -195,7 +198,9 @@ __global__ __launch_bounds__(128) void gram_mfma_kernel(const float *__restrict_
                 for (int r = 0; r < 4; ++r) {
                     const int i = 16 * b + 4 * q + r;
                     const int j = 16 * b2 + c16;
-                    const float v = acc[p][r] + xch[(p * 4 + r) * 64 + lane];
+                    float v = acc[p][r];
+#pragma unroll
+                    for (int w = 1; w < kGramWaves; ++w) v += xch[((w - 1) * NPAIR * 4 + p * 4 + r) * 64 + lane];
                     if (i <= j && j < n) out[tri(i, j, n)] = v;
                 }
                 ++p;

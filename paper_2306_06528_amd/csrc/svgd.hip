@@ -180,16 +180,16 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
 #undef CALL
     } else {
         KernelTimer t(c, SVGD_KERNEL_GRAM, s);
-        const int64_t ntile = (D + 127) / 128;
-        nparts = clampi(ntile, 1, c->num_cu * 4);
+        const int64_t ntile = (D + 64 * kGramWaves - 1) / (64 * kGramWaves);
+        nparts = clampi(ntile, 1, c->num_cu * 2);
         mode = kModeGram;
         const int NB = (n + 15) / 16;
         if (NB == 2)
-            gram_mfma_kernel<2><<<nparts, 128, 0, s>>>(X, n, D, c->partials);
+            gram_mfma_kernel<2><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
         else if (NB == 3)
-            gram_mfma_kernel<3><<<nparts, 128, 0, s>>>(X, n, D, c->partials);
+            gram_mfma_kernel<3><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
         else
-            gram_mfma_kernel<4><<<nparts, 128, 0, s>>>(X, n, D, c->partials);
+            gram_mfma_kernel<4><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
