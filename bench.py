@@ -102,7 +102,7 @@ def main():
         torch.cuda.synchronize()
         del scratch
 
-    carry = (not args.separate_gram) and n > 16
+    carry = not args.separate_gram
     with svgd.Svgd(n, D, 0, flags=svgd.FLAG_CARRY_GRAM if carry else 0) as eng:
         for _ in range(args.warmup):
             eng.step(X, G, eps, stream=stream)

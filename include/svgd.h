@@ -55,8 +55,7 @@ enum svgd_status {
  * also accumulates the pairwise sums of the NEW X, and the next svgd_step on the same (X, n, D)
  * skips its own pass over X.  The caller promises that between two svgd_step calls X is modified
  * by nobody else; after touching X (or to be safe) call svgd_forget_carry.  svgd_bandwidth and
- * svgd_phi always recompute from X and drop the carried sums.  Effective for n > 16 only; for
- * smaller n the flag is accepted and ignored.
+ * svgd_phi always recompute from X and drop the carried sums.
  */
 #define SVGD_FLAG_CARRY_GRAM 1u
 

@@ -132,11 +132,11 @@ void launch_gram_valu(const float *X, int64_t D, float *partials, int grid, hipS
     gram_valu_kernel<N><<<grid, 256, 0, s>>>(X, D, partials);
 }
 
-template <int N, bool EMIT>
+template <int N, bool EMIT, bool CARRY>
 void launch_update_valu(float *X, const float *G, float *PHI, const float *coef, const DevState *st,
-                        int64_t D, float eps, int grid, hipStream_t s)
+                        int64_t D, float eps, float *gram_out, int grid, hipStream_t s)
 {
-    update_valu_kernel<N, EMIT><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, eps);
+    update_valu_kernel<N, EMIT, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, eps, gram_out);
 }
 
 #define SVGD_SWITCH_N(n, CALL)                                                                     \
@@ -169,7 +169,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
     int nparts, mode;
     if (use_carry) {
         nparts = c->carry_nparts;
-        mode = kModeGram;
+        mode = (n <= 8) ? kModeDiff : kModeGram; // the update kernels mirror the Gram kernels' formats
     } else if (n <= 16) {
         const int64_t ngroups = (D + 3) / 4;
         nparts = clampi((ngroups + 255) / 256, 1, c->num_cu * 4);
@@ -220,8 +220,11 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
     KernelTimer t(c, SVGD_KERNEL_UPDATE, s);
     if (n <= 16) {
         const int64_t ngroups = (D + 3) / 4;
-        const int grid = clampi((ngroups + 255) / 256, 1, c->num_cu * 8);
-#define CALL(N) launch_update_valu<N, EMIT>(X, G, PHI, c->coef, c->state, D, eps, grid, s)
+        // fewer, longer-lived workgroups when each one ends with a reduction of its pair sums
+        const int per_cu = CARRY ? 4 : 8;
+        const int grid = clampi((ngroups + 255) / 256, 1, c->num_cu * per_cu < kMaxParts ? c->num_cu * per_cu : kMaxParts);
+        if (CARRY) c->carry_nparts = grid;
+#define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, eps, c->partials, grid, s)
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
     } else {
@@ -373,7 +376,7 @@ int svgd_step(svgd_handle_t c, float *X, const float *G, int n, int64_t D, float
     if (overlaps(X, G, n, D)) return SVGD_ERR_INVALID_ARG;
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
-    const bool carry_mode = (c->flags & SVGD_FLAG_CARRY_GRAM) && n > 16;
+    const bool carry_mode = (c->flags & SVGD_FLAG_CARRY_GRAM) != 0;
     const bool use_carry = carry_mode && c->carry_valid && c->carry_X == X && c->carry_n == n && c->carry_D == D;
     c->carry_valid = false;
     rc = run_kernel_matrix(c, X, n, D, s, use_carry);

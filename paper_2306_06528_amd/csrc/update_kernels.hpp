@@ -21,14 +21,24 @@ namespace svgd {
 // n <= 16: vector ALU, lanes = columns, 4 consecutive columns per thread (16-byte loads, 1 KiB
 // contiguous per row per wave).  C and rho are wave-uniform and read through scalar loads.
 // ---------------------------------------------------------------------------------------------
-template <int N, bool EMIT>
+template <int N, bool EMIT, bool CARRY>
 __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
                                                           const float *__restrict__ G,
                                                           float *__restrict__ PHI,
                                                           const float *__restrict__ coef,
                                                           const DevState *__restrict__ st,
-                                                          int64_t D, float eps)
+                                                          int64_t D, float eps,
+                                                          float *__restrict__ gram_out)
 {
+    static_assert(!(CARRY && EMIT), "the pair sums are carried only when X is updated");
+    // CARRY: the pair sums of the UPDATED columns, in the format of gram_valu_kernel<N>
+    constexpr bool kDiff = (N <= 8);
+    constexpr int P = N * (N + 1) / 2;
+    float pacc[CARRY ? P : 1];
+    if constexpr (CARRY) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) pacc[p] = 0.f;
+    }
     const float c2h = st->two_over_h;
     const float *__restrict__ C = coef + kOffC;
     const float *__restrict__ rho = coef + kOffRho;
@@ -43,18 +53,56 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
             x[j] = load4(X + (int64_t)j * D, col, D, full);
             z[j] = load4_stream(G + (int64_t)j * D, col, D, full);
         }
+        f32x4 m = f32x4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (CARRY && !kDiff) { // centre by the pre-update column mean
+#pragma unroll
+            for (int j = 0; j < N; ++j) m += x[j];
+            m *= (1.0f / N);
+        }
 #pragma unroll
         for (int j = 0; j < N; ++j) z[j] -= c2h * x[j];
+        f32x4 y[CARRY ? N : 1];
 #pragma unroll
         for (int i = 0; i < N; ++i) {
             f32x4 acc = rho[i] * x[i];
 #pragma unroll
             for (int j = 0; j < N; ++j) acc += C[i * N + j] * z[j];
-            if constexpr (EMIT)
+            if constexpr (EMIT) {
                 store4(PHI + (int64_t)i * D, col, D, full, acc);
-            else
-                store4(X + (int64_t)i * D, col, D, full, x[i] + eps * acc);
+            } else {
+                const f32x4 xn = x[i] + eps * acc;
+                store4(X + (int64_t)i * D, col, D, full, xn);
+                if constexpr (CARRY) y[i] = xn - m; // columns beyond D: x = g = 0 -> xn = 0, m = 0
+            }
         }
+        if constexpr (CARRY) {
+#pragma unroll
+            for (int i = 0; i < N; ++i) {
+#pragma unroll
+                for (int j = kDiff ? i + 1 : i; j < N; ++j) {
+                    const f32x4 u = kDiff ? y[i] - y[j] : y[i];
+                    const f32x4 v = kDiff ? u : y[j];
+                    float a = pacc[tri(i, j, N)];
+                    a = fmaf(u.x, v.x, a);
+                    a = fmaf(u.y, v.y, a);
+                    a = fmaf(u.z, v.z, a);
+                    a = fmaf(u.w, v.w, a);
+                    pacc[tri(i, j, N)] = a;
+                }
+            }
+        }
+    }
+    if constexpr (CARRY) {
+        __shared__ float red[4][P];
+        const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const float v = wave_sum(pacc[p]);
+            if (lane == 0) red[wave][p] = v;
+        }
+        __syncthreads();
+        for (int p = threadIdx.x; p < P; p += 256)
+            gram_out[(int64_t)blockIdx.x * P + p] = (red[0][p] + red[1][p]) + (red[2][p] + red[3][p]);
     }
 }
 

@@ -294,7 +294,9 @@ def test_config5_large_ensemble_full_size(svgd):
 # carried Gram (SVGD_FLAG_CARRY_GRAM): step t's update also accumulates the pair sums of the new
 # X, and step t+1 skips its own pass over X
 # ----------------------------------------------------------------------------------------------
-@pytest.mark.parametrize("n,D", [(64, 70_001), (32, 4096), (17, 1531), (48, 129), (33, 200_000), (64, 63)])
+@pytest.mark.parametrize("n,D", [(64, 70_001), (32, 4096), (17, 1531), (48, 129), (33, 200_000), (64, 63),
+                                 (8, 100_003), (4, 1024), (16, 8577), (12, 70_001), (1, 100), (2, 65),
+                                 (8, 3_000_017)])
 def test_carried_gram_matches_oracle_every_step(svgd, n, D):
     X, G = _random_problem(n, D, 31 * n + D, x_std=0.3)
     eps = 0.05
