@@ -25,10 +25,11 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
     # (config, carried Gram?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True): (4081915.6, 2803354.8),
+    (5, True): (4081995.9, 2803354.3),
+    (5, False): (4069151.3, 2795026.4),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "6440bbe400d155b62ef4d92ca10eb2b58ab8487427c32c0bc10559d044679988"
+TRAFFIC_SOURCE_SHA256 = "a6f03f7ebfda969c3f780657c197a452f11b344e73f85cc1a32a02964e2c2a70"
 
 
 def kernel_source_hash():
