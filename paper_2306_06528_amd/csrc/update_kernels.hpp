@@ -282,11 +282,16 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     const uint32_t a0 = (uint32_t)(reinterpret_cast<uintptr_t>(OUT) >> 2) & 31u;
 
     // Software pipeline across tiles: the loads of tile t+1 are issued while tile t is being
-    // multiplied, into registers as they fall free - x rows of block bi after that block's
-    // epilogue, g rows of step group sg after the last block has consumed them.  The last tile of
-    // the range "prefetches" itself again (a few KB that nobody uses) so that the steady-state
-    // code has no branch.
-    f32x4 x[NS], z[NS];
+    // multiplied.  Two schedules, chosen by measurement:
+    //   DBUF (NB <= 2): all of them at the top of tile t into a second set of registers - small
+    //     tiles are short, and the loads need the whole tile time to come back;
+    //   otherwise: into the registers of tile t as they fall free - x rows of block bi after that
+    //     block's epilogue, g rows of step group sg after the last block has consumed them (more
+    //     requests in flight only added HBM contention at n = 64).
+    // The last tile of the range "prefetches" itself again (a few KB that nobody uses) so that the
+    // steady-state code has no branch.
+    constexpr bool DBUF = (NB <= 2);
+    f32x4 x[NS], z[NS], xn[DBUF ? NS : 1], gn[DBUF ? NS : 1];
     auto load_x = [&](const float *xt, int s) __attribute__((always_inline)) {
         const int urow = 16 * (s >> 2) + (s & 3); // uniform part of the row index
         if (FULLROWS || urow + 4 * q < n) x[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * D);
@@ -295,6 +300,18 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         const int urow = 16 * (s >> 2) + (s & 3);
         if (FULLROWS || urow + 4 * q < n) z[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * D);
     };
+    auto load_next = [&](const float *xt, const float *gt) __attribute__((always_inline)) {
+        if constexpr (DBUF) {
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                const int urow = 16 * (s >> 2) + (s & 3);
+                if (FULLROWS || urow + 4 * q < n) {
+                    xn[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * D);
+                    gn[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * D);
+                }
+            }
+        }
+    };
     if (t0 < t1) {
         int64_t in_off = in_lane + c_begin;
         opaque(in_off);
@@ -302,9 +319,15 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         for (int s = 0; s < NS; ++s) {
             x[s] = f32x4{0.f, 0.f, 0.f, 0.f};
             z[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-            load_x(X + in_off, s);
-            load_g(G + in_off, s);
+            if constexpr (DBUF) {
+                xn[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+                gn[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            } else {
+                load_x(X + in_off, s);
+                load_g(G + in_off, s);
+            }
         }
+        load_next(X + in_off, G + in_off);
     }
 
     auto process_tile = [&](auto first_tag, int64_t tile) __attribute__((always_inline)) {
@@ -317,6 +340,15 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         opaque(in_off);
         const float *xt = X + in_off, *gt = G + in_off;
         float *ot = OUT + out_off;
+
+        if constexpr (DBUF) { // this tile's data becomes current, the next tile's loads go out
+#pragma unroll
+            for (int s = 0; s < NS; ++s) {
+                x[s] = xn[s];
+                z[s] = gn[s];
+            }
+            load_next(xt, gt);
+        }
 
         f32x4 mg[CARRY ? 4 : 1];      // pre-update column means in the Gram operand layout
         f32x4 ag[CARRY ? NB : 1][4];  // Gram operands of the blocks finished so far
@@ -397,7 +429,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
                         acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[k], z[4 * sg + k][t], acc[t], 0, 0, 0);
-                if (bi == NB - 1) { // z rows 4sg..4sg+3 are dead: fetch the next tile's g
+                if (!DBUF && bi == NB - 1) { // z rows 4sg..4sg+3 are dead: fetch the next tile's g
 #pragma unroll
                     for (int k = 0; k < 4; ++k) load_g(gt, 4 * sg + k);
                 }
@@ -424,9 +456,10 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 }
                 *reinterpret_cast<f32x4 *>(&cur[cur_index(4 * q + r, 4 * c16)]) = o;
             }
-            // x rows of this block are dead: fetch the next tile's
+            if constexpr (!DBUF) { // x rows of this block are dead: fetch the next tile's
 #pragma unroll
-            for (int r = 0; r < 4; ++r) load_x(xt, 4 * bi + r);
+                for (int r = 0; r < 4; ++r) load_x(xt, 4 * bi + r);
+            }
             if constexpr (CARRY) {
                 // lane (q, rr = c16) takes row rr of this block, columns 4(4st + q)..+3, centred
 #pragma unroll
