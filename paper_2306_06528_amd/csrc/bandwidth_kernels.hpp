@@ -43,9 +43,8 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
     __syncthreads();
 
     // d2 per pair: direct sums, or S_ii + S_jj - 2 S_ij (clamped at 0) from the centred Gram
-    for (int e = tid; e < n * n; e += kBwThreads) {
-        const int i = e / n, j = e % n;
-        if (i < j) {
+    for (int i = tid >> 6; i < n; i += kBwThreads / 64) {   // wave -> row, lane -> column
+        for (int j = i + 1 + (tid & 63); j < n; j += 64) {
             double d;
             if (mode == kModeDiff) {
                 d = S[tri(i, j, n)];
@@ -80,7 +79,12 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
                         S[b2] = va;
                     }
                 }
-                __syncthreads();
+                // M/2 <= kBwThreads, so a thread owns one pair per stage and a wave's 64 pairs at
+                // distance j < 64 lie in its own 128-element block: such stages exchange data
+                // only inside the wave (whose LDS operations execute in order) and need no barrier
+                // unless a wider stage precedes or follows.
+                const int next_j = (j > 1) ? (j >> 1) : k;
+                if (j >= 64 || next_j >= 64) __syncthreads();
             }
         }
         if (tid == 0) {
@@ -105,6 +109,7 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
     __syncthreads();
     const double h = h_sh;
     const double c2h = (n == 1) ? 0.0 : 2.0 / h;
+    const double inv_n = 1.0 / (double)n;
 
     for (int e = tid; e < Pp; e += kBwThreads) S[e] = exp(-pr[e] / h); // K per pair, reusing S
     __syncthreads();
@@ -112,13 +117,14 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
         double r = 1.0;
         for (int j = 0; j < n; ++j)
             if (j != tid) r += S[tid < j ? pair_index(tid, j, n) : pair_index(j, tid, n)];
-        coef[kOffRho + tid] = (float)(c2h * r / (double)n);
+        coef[kOffRho + tid] = (float)(c2h * r * inv_n);
     }
-    for (int e = tid; e < n * n; e += kBwThreads) {
-        const int i = e / n, j = e % n;
-        const double k = (i == j) ? 1.0 : S[i < j ? pair_index(i, j, n) : pair_index(j, i, n)];
-        coef[kOffK + e] = (float)k;
-        coef[kOffC + e] = (float)(k / (double)n);
+    for (int i = tid >> 6; i < n; i += kBwThreads / 64) {   // wave -> row, lane -> column
+        for (int j = tid & 63; j < n; j += 64) {
+            const double k = (i == j) ? 1.0 : S[i < j ? pair_index(i, j, n) : pair_index(j, i, n)];
+            coef[kOffK + i * n + j] = (float)k;
+            coef[kOffC + i * n + j] = (float)(k * inv_n);
+        }
     }
     // A operands of v_mfma_f32_16x16x4_f32 for the matrix-core update kernel: for output block
     // bi and step s = 4b + r, lane (q = lane/16, m = lane%16) holds C[16bi + m][16b + 4q + r].
@@ -133,7 +139,7 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
             const int j = 16 * (s >> 2) + 4 * (lane >> 4) + (s & 3);
             double c = 0.0;
             if (i < n && j < n)
-                c = ((i == j) ? 1.0 : S[i < j ? pair_index(i, j, n) : pair_index(j, i, n)]) / (double)n;
+                c = ((i == j) ? 1.0 : S[i < j ? pair_index(i, j, n) : pair_index(j, i, n)]) * inv_n;
             coef[kOffAT + e] = (float)c;
         }
     }
