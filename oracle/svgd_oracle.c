@@ -156,3 +156,22 @@ void oracle_step(const void *X, const void *G, int is_f64, int n, int64_t D, dou
     free(K);
     free(r);
 }
+
+/*
+ * SWAG / multi-SWAG running moments (paper Sec. 2: SWAG keeps the first and second moments of a
+ * network's parameter trajectory; multi-SWAG does so for every particle of an ensemble).
+ * After `count` earlier updates the running means absorb one more iterate x (the published SWAG
+ * recursion of Maddox et al.):
+ *     mean <- (count * mean + x) / (count + 1),    sq <- (count * sq + x^2) / (count + 1)
+ * for every entry of the n x D particle matrix.  mean and sq are fp64 arrays updated in place.
+ */
+void oracle_swag_update(double *mean, double *sq, const void *X, int is_f64, int64_t total, int64_t count)
+{
+    const double c = (double)count;
+#pragma omp parallel for schedule(static)
+    for (int64_t e = 0; e < total; ++e) {
+        double x = ld(X, is_f64, e);
+        mean[e] = (c * mean[e] + x) / (c + 1.0);
+        sq[e] = (c * sq[e] + x * x) / (c + 1.0);
+    }
+}

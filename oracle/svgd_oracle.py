@@ -30,6 +30,7 @@ _lib.oracle_bandwidth.restype = _d
 _lib.oracle_kernel.argtypes = [_dp, _i, _d, _dp, _dp]
 _lib.oracle_phi_cols.argtypes = [_vp, _vp, _i, _i, _i64, _dp, _d, _i64, _i64, _dp]
 _lib.oracle_step.argtypes = [_vp, _vp, _i, _i, _i64, _d, _d, _dp, _dp, _dp, _dp, _dp, _dp]
+_lib.oracle_swag_update.argtypes = [_dp, _dp, _vp, _i, _i64, _i64]
 
 
 def num_threads() -> int:
@@ -104,3 +105,13 @@ def step(X, G, eps, h_fixed=0.0, want_phi=True, want_xnew=True):
                      _dptr(d2), _dptr(K), _dptr(r), ctypes.byref(h),
                      _dptr(phi) if want_phi else None, _dptr(xn) if want_xnew else None)
     return dict(d2=d2, K=K, r=r, h=h.value, phi=phi, X_new=xn)
+
+
+def swag_update(mean, sq, X, count):
+    """SWAG running moments, in place: mean, sq are float64 arrays shaped like X (float32/64);
+    `count` iterates have been absorbed before this one (paper Sec. 2; Maddox et al.'s recursion)."""
+    X = _prep(X)
+    assert mean.dtype == np.float64 and sq.dtype == np.float64
+    assert mean.shape == X.shape and sq.shape == X.shape
+    assert mean.flags.c_contiguous and sq.flags.c_contiguous
+    _lib.oracle_swag_update(_dptr(mean), _dptr(sq), _ptr(X), int(X.dtype == np.float64), X.size, int(count))
