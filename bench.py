@@ -66,6 +66,54 @@ def cpu_baseline(wl):
     }
 
 
+def run_swag(args, wl, X, svgd, torch):
+    """One "step" = one swag_update_moments call over all n x D parameters (20 B per parameter)."""
+    n, D = wl.n, wl.D
+    mean = torch.zeros_like(X)
+    sq = torch.zeros_like(X)
+    for t in range(args.warmup):
+        svgd.swag_update_moments(mean, sq, X, t)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for t in range(args.steps):
+        svgd.swag_update_moments(mean, sq, X, args.warmup + t)
+    e1.record()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    kern_ms = e0.elapsed_time(e1) / args.steps     # back-to-back launches of the one kernel
+    gbs = 20 * n * D / (kern_ms * 1e-3) / 1e9
+    out = {
+        "metric": "multi-SWAG particle-params absorbed into running moments/s",
+        "value": n * D * args.steps / dt, "unit": "particle-params/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": dt * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{wl.cfg.name}: moments of n={n} particles x D={D} fp32", "n": n, "D": D,
+                   "config_index": args.config},
+        "roofline": {"kernel": "swag_moments_kernel", "bound": "hbm", "achieved": gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gbs / HBM_PEAK_GBS, "traffic": None},
+    }
+    if not args.no_cpu_baseline:
+        import numpy as np
+        from oracle import svgd_oracle
+        ds = int(min(D, 4_000_000))
+        Xs = X[:, :ds].contiguous().cpu().numpy()
+        m = np.zeros(Xs.shape)
+        s2 = np.zeros(Xs.shape)
+        c0 = time.perf_counter()
+        reps = 4
+        for t in range(reps):
+            svgd_oracle.swag_update(m, s2, Xs, t)
+        cdt = time.perf_counter() - c0
+        out["cpu_baseline"] = {"value": n * ds * reps / cdt, "unit": "particle-params/s",
+                               "cores": svgd_oracle.num_threads(), "kind": "oracle",
+                               "sample": f"{reps} fp64 oracle updates on the first {ds} of {D} columns, "
+                                         f"all {n} particles ({cdt:.1f} s)"}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +124,8 @@ def main():
     ap.add_argument("--separate-gram", action="store_true",
                     help="run the pairwise-d2 pass as its own kernel every step instead of carrying "
                          "the sums over from the previous update (SVGD_FLAG_CARRY_GRAM)")
+    ap.add_argument("--swag", action="store_true",
+                    help="time the multi-SWAG running-moments kernel on the config's n x D instead of svgd_step")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the plain copy kernel once over G (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -96,6 +146,10 @@ def main():
     X = wl.X0.clone()
     G = wl.score(X, 0).clone()
     stream = torch.cuda.current_stream()
+
+    if args.swag:
+        run_swag(args, wl, X, svgd, torch)
+        return
 
     if args.calibrate_copy:
         scratch = torch.empty_like(G)

@@ -131,6 +131,20 @@ int svgd_profile_end(svgd_handle_t h, double *ms_sum, int *count);
  */
 int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream);
 
+/*
+ * Multi-SWAG running moments (paper Sec. 2: SWAG keeps the first and second moments of a
+ * network's parameter trajectory, multi-SWAG for every particle of the ensemble).  Absorbs one
+ * more iterate X (DEVICE, n x D fp32, row-major, contiguous) into the running means after `count`
+ * earlier updates (count = 0 overwrites them):
+ *     mean <- (count*mean + x)/(count+1),   sqmean <- (count*sqmean + x*x)/(count+1),
+ * in place in mean and sqmean (DEVICE, same shape as X, caller-owned, must not overlap X or each
+ * other).  The diagonal SWAG covariance is sqmean - mean^2.  Needs no handle; enqueued on `stream`
+ * of the current device; does not synchronise or allocate.  INVALID_ARG: null pointer, n < 1,
+ * D < 1, count < 0, overlapping arrays.
+ */
+int swag_update_moments(float *mean, float *sqmean, const float *X, int n, int64_t D, int64_t count,
+                        void *stream);
+
 /* Free the handle's scratch and invalidate the handle.  The caller synchronises beforehand. */
 int svgd_destroy(svgd_handle_t h);
 

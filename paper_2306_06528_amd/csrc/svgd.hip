@@ -11,6 +11,7 @@
 #include "bandwidth_kernels.hpp"
 #include "common.hpp"
 #include "gram_kernels.hpp"
+#include "swag_kernels.hpp"
 #include "update_kernels.hpp"
 
 using namespace svgd;
@@ -429,6 +430,24 @@ int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream)
     if (!dst || !src || nbytes < 16 || (nbytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15))
         return SVGD_ERR_INVALID_ARG;
     diag_copy_kernel<<<2048, 256, 0, (hipStream_t)stream>>>((const f32x4 *)src, (f32x4 *)dst, nbytes >> 4);
+    return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
+}
+
+int swag_update_moments(float *mean, float *sqmean, const float *X, int n, int64_t D, int64_t count,
+                        void *stream)
+{
+    if (!mean || !sqmean || !X || n < 1 || D < 1 || count < 0) return SVGD_ERR_INVALID_ARG;
+    if (overlaps(mean, X, n, D) || overlaps(sqmean, X, n, D) || overlaps(mean, sqmean, n, D))
+        return SVGD_ERR_INVALID_ARG;
+    const int64_t total = (int64_t)n * D;
+    const int64_t ngroups = (total + 3) / 4;
+    int cus = 0, dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+        return SVGD_ERR_DEVICE;
+    const int grid = clampi((ngroups + 255) / 256, 1, cus * 8);
+    const float inv = (float)(1.0 / ((double)count + 1.0));
+    swag_moments_kernel<<<grid, 256, 0, (hipStream_t)stream>>>(mean, sqmean, X, total, inv, count == 0);
     return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
 }
 

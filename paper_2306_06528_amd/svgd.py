@@ -32,6 +32,9 @@ _lib.svgd_get_last.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.c_voi
 _lib.svgd_destroy.argtypes = [_H]
 _lib.svgd_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
 _lib.svgd_diag_copy.restype = ctypes.c_int
+_lib.swag_update_moments.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
+                                     ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p]
+_lib.swag_update_moments.restype = ctypes.c_int
 _lib.svgd_profile_begin.argtypes = [_H]
 _lib.svgd_profile_end.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
 _lib.svgd_last_device_error.argtypes = [_H]
@@ -79,6 +82,18 @@ def diag_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):
     if dst.numel() * dst.element_size() != nbytes:
         raise ValueError("dst and src must have the same size in bytes")
     rc = _lib.svgd_diag_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream))
+    if rc != SVGD_OK:
+        raise SvgdError(rc)
+
+
+def swag_update_moments(mean: torch.Tensor, sqmean: torch.Tensor, X: torch.Tensor, count: int, stream=None):
+    """Multi-SWAG running moments: absorb X into mean / sqmean (in place) after `count` updates."""
+    X, mean, sqmean = _dev_matrix(X, "X"), _dev_matrix(mean, "mean"), _dev_matrix(sqmean, "sqmean")
+    if mean.shape != X.shape or sqmean.shape != X.shape:
+        raise ValueError("mean, sqmean and X must have the same shape")
+    n, D = X.shape
+    rc = _lib.swag_update_moments(mean.data_ptr(), sqmean.data_ptr(), X.data_ptr(), n, D, int(count),
+                                  _stream_ptr(stream))
     if rc != SVGD_OK:
         raise SvgdError(rc)
 

@@ -22,12 +22,12 @@ def lib():
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(svgd_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b((?:svgd|swag)_[a-z_]+)\s*\(", text)))
 
 
 def test_header_declares_the_four_calls():
     names = declared_functions()
-    for f in ("svgd_create", "svgd_bandwidth", "svgd_step", "svgd_destroy"):
+    for f in ("svgd_create", "svgd_bandwidth", "svgd_step", "svgd_destroy", "swag_update_moments"):
         assert f in names
 
 
