@@ -175,6 +175,21 @@ def main():
         prof = eng.profile_end()
         torch.cuda.synchronize()
 
+    # for reference, the same workload with the pairwise-d2 pass as its own kernel every step
+    alt = None
+    if carry:
+        with svgd.Svgd(n, D, 0) as eng2:
+            for _ in range(args.warmup):
+                eng2.step(X, G, eps, stream=stream)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                eng2.step(X, G, eps, stream=stream)
+            torch.cuda.synchronize()
+            dt2 = time.perf_counter() - t0
+        alt = {"gram": "separate pass", "ms_per_step": dt2 * 1e3 / args.steps,
+               "value": n * D * args.steps / dt2}
+
     assert torch.isfinite(X).all().item(), "X went non-finite during the benchmark"
     ms_per_step = dt * 1e3 / args.steps
     value = n * D * args.steps / dt
@@ -208,6 +223,7 @@ def main():
         "step_hbm_frac": (UPDATE_BYTES_PER_PARAM if carry else STEP_BYTES_PER_PARAM) * n * D
                          / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": kern_ms,
+        "separate_gram": alt,
         "gram_gbs": gram_gbs,
         "roofline": {
             "kernel": "update_mfma_kernel (fused K.[G|X] in-place update" +

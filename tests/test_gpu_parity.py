@@ -366,3 +366,37 @@ def test_full_size_carried_gram(svgd, cfg_index):
         want = X1[:, s:s + 4096].astype(np.float64) + wl.cfg.eps * phi
         err = np.abs(X2[:, s:s + 4096] - want).max() / np.abs(want).max()
         assert err <= 1e-6
+
+
+@pytest.mark.parametrize("n", [8, 32, 64])
+@pytest.mark.parametrize("shift", [1, 3, 17])
+def test_buffers_with_odd_base_alignment(svgd, n, shift):
+    """X, G and PHI that start `shift` floats into their allocations (each with a different
+    shift): the store windows of the update are aligned per row from the actual addresses."""
+    D = 5003
+    g = torch.Generator(device="cuda")
+    g.manual_seed(n + shift)
+    bufs = [torch.zeros(n * D + 64, device="cuda") for _ in range(3)]
+    offs = [shift, shift + 2, shift + 5]
+    X, G, PHI = [b[o:o + n * D].view(n, D) for b, o in zip(bufs, offs)]
+    X.copy_(torch.randn(n, D, generator=g, device="cuda"))
+    G.copy_(torch.randn(n, D, generator=g, device="cuda"))
+    Xh, Gh = X.cpu().numpy(), G.cpu().numpy()
+    ref = orc.step(Xh, Gh, 0.01)
+    for flags in (0, svgd.FLAG_CARRY_GRAM):
+        Xw = bufs[0].clone()[offs[0]:offs[0] + n * D].view(n, D)
+        guard = Xw.storage_offset()
+        with svgd.Svgd(n, D, flags=flags) as eng:
+            eng.phi(Xw, G, PHI)
+            eng.step(Xw, G, 0.01)
+            eng.step(Xw, G, 0.0)     # second step (carried sums when flagged); eps = 0 leaves X as is
+            torch.cuda.synchronize()
+        e = np.abs(PHI.cpu().numpy() - ref["phi"]).max() / np.abs(ref["phi"]).max()
+        assert e <= TOL_PHI
+        err = np.abs(Xw.cpu().numpy() - ref["X_new"]).max() / np.abs(ref["X_new"]).max()
+        assert err <= 1e-6
+        # nothing outside the n*D window was touched
+        base = Xw._base if Xw._base is not None else Xw
+        flat = base.view(-1)
+        assert torch.all(flat[:guard] == 0) and torch.all(flat[guard + n * D:] == 0)
+    assert torch.all(bufs[2][:offs[2]] == 0) and torch.all(bufs[2][offs[2] + n * D:] == 0)
