@@ -29,12 +29,7 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
 
     const int64_t ngroups = (D + 3) >> 2;
     const int64_t nthreads = (int64_t)gridDim.x * 256;
-    for (int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x; grp < ngroups; grp += nthreads) {
-        const int64_t col = grp << 2;
-        const bool full = (col + 4 <= D);
-        f32x4 x[N];
-#pragma unroll
-        for (int j = 0; j < N; ++j) x[j] = load4(X + (int64_t)j * D, col, D, full);
+    auto accumulate = [&](f32x4 (&x)[N]) __attribute__((always_inline)) {
         if constexpr (kDiff) {
 #pragma unroll
             for (int i = 0; i < N; ++i) {
@@ -69,6 +64,20 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
                 }
             }
         }
+    };
+    // two column groups per iteration when the registers allow: twice the loads in flight
+    constexpr int U = (N <= 8) ? 2 : 1;
+    for (int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x; grp < ngroups; grp += U * nthreads) {
+        f32x4 x[U][N];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t col = (grp + u * nthreads) << 2; // past the end: every load is masked to 0
+            const bool full = (col + 4 <= D);
+#pragma unroll
+            for (int j = 0; j < N; ++j) x[u][j] = load4(X + (int64_t)j * D, col, D, full);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) accumulate(x[u]);
     }
 
     __shared__ float red[4][P];

@@ -173,7 +173,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
         mode = (n <= 8) ? kModeDiff : kModeGram; // the update kernels mirror the Gram kernels' formats
     } else if (n <= 16) {
         const int64_t ngroups = (D + 3) / 4;
-        nparts = clampi((ngroups + 255) / 256, 1, c->num_cu * 4);
+        nparts = clampi((ngroups + 255) / 256, 1, c->num_cu * 3); // all resident at once; each ends with a reduction
         mode = (n <= 8) ? kModeDiff : kModeGram;
         KernelTimer t(c, SVGD_KERNEL_GRAM, s);
 #define CALL(N) launch_gram_valu<N>(X, D, c->partials, nparts, s)
