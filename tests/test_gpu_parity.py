@@ -400,3 +400,39 @@ def test_buffers_with_odd_base_alignment(svgd, n, shift):
         flat = base.view(-1)
         assert torch.all(flat[:guard] == 0) and torch.all(flat[guard + n * D:] == 0)
     assert torch.all(bufs[2][:offs[2]] == 0) and torch.all(bufs[2][offs[2] + n * D:] == 0)
+
+
+@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("n,D", [(4, 1024), (32, 20_001)])
+def test_step_can_be_captured_in_a_graph(svgd, n, D, flags):
+    """svgd_step neither allocates nor synchronises, so a caller may capture it in a HIP graph.
+    The graph is replayed several times with eager work and synchronisations in between, and
+    every replay is compared with the same number of eager steps."""
+    X0, G = _random_problem(n, D, 11 * n + flags, x_std=0.2)
+    eps = 0.02
+    # eager reference trajectory
+    Xe = X0.clone()
+    with svgd.Svgd(n, D, flags=flags) as eng:
+        ref = []
+        for _ in range(5):
+            eng.step(Xe, G, eps)
+            ref.append(Xe.clone())
+    Xg = X0.clone()
+    with svgd.Svgd(n, D, flags=flags) as eng:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            eng.step(Xg, G, eps, stream=side)          # warm-up on the capture stream (step 1)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            eng.step(Xg, G, eps)                       # captured, not executed
+        assert torch.equal(Xg, ref[0])
+        for k in range(1, 5):
+            graph.replay()
+            torch.cuda.synchronize()
+            junk = torch.randn(1000, device="cuda").sum().item()   # eager work between replays
+            assert np.isfinite(junk)
+            err = (Xg - ref[k]).abs().max().item() / ref[k].abs().max().item()
+            assert err <= 1e-6, f"replay {k}: {err:.3e}"
