@@ -128,7 +128,7 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
     }
     // A operands of v_mfma_f32_16x16x4_f32 for the matrix-core update kernel: for output block
     // bi and step s = 4b + r, lane (q = lane/16, m = lane%16) holds C[16bi + m][16b + 4q + r].
-    if (n > 16) {
+    if (n > kValuMaxN) {
         const int NB = (n + 15) / 16;
         const int total = NB * 4 * NB * kWave;
         for (int e = tid; e < total; e += kBwThreads) {

@@ -8,6 +8,10 @@ namespace svgd {
 constexpr int kMaxN = 64;                              // particles
 constexpr int kMaxPairsFull = kMaxN * (kMaxN + 1) / 2; // upper triangle with diagonal
 constexpr int kWave = 64;
+// n <= kValuMaxN runs on the vector ALU (one accumulator per pair in registers); larger n on the
+// matrix cores, padded to a multiple of 16 rows.  Above 12 the register budget of the vector
+// kernels (pair sums carried across steps included) no longer fits without spilling.
+constexpr int kValuMaxN = 12;
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 // rows of X start at i*D floats, so a 4-column group is only 4-byte aligned in general

@@ -9,7 +9,7 @@
 namespace svgd {
 
 // ---------------------------------------------------------------------------------------------
-// n <= 16: vector ALU, lanes = columns.  Each thread loads 4 consecutive columns of every row
+// n <= kValuMaxN (12): vector ALU, lanes = columns.  Each thread loads 4 consecutive columns of every row
 // (one 16-byte load per row, 1 KiB contiguous per row per wave) and keeps one fp32 accumulator
 // per pair in registers.
 //   N <= 8 : direct differences (x_i - x_j)^2 - no cancellation at all.
@@ -93,7 +93,7 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
-// 16 < n <= 64: matrix cores.  The Gram S = Y Y^T of the column-centred Y is a contraction over
+// kValuMaxN < n <= 64: matrix cores.  The Gram S = Y Y^T of the column-centred Y is a contraction over
 // columns, so the MFMA A and B operands are both "lane = (particle row, column slot)".  Loading
 // that shape straight from HBM would touch 16 rows per quarter-wave, so each wave instead
 //   1. loads a 16*NB-row x 64-column slab with row-contiguous 16-byte loads (256 B per row per

@@ -153,11 +153,7 @@ void launch_update_valu(float *X, const float *G, float *PHI, const float *coef,
     case 9: CALL(9); break;                                                                        \
     case 10: CALL(10); break;                                                                      \
     case 11: CALL(11); break;                                                                      \
-    case 12: CALL(12); break;                                                                      \
-    case 13: CALL(13); break;                                                                      \
-    case 14: CALL(14); break;                                                                      \
-    case 15: CALL(15); break;                                                                      \
-    default: CALL(16); break;                                                                      \
+    default: CALL(12); break;                                                                      \
     }
 
 int clampi(int64_t v, int lo, int hi) { return (int)(v < lo ? lo : (v > hi ? hi : v)); }
@@ -171,7 +167,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
     if (use_carry) {
         nparts = c->carry_nparts;
         mode = (n <= 8) ? kModeDiff : kModeGram; // the update kernels mirror the Gram kernels' formats
-    } else if (n <= 16) {
+    } else if (n <= kValuMaxN) {
         const int64_t ngroups = (D + 3) / 4;
         nparts = clampi((ngroups + 255) / 256, 1, c->num_cu * 3); // all resident at once; each ends with a reduction
         mode = (n <= 8) ? kModeDiff : kModeGram;
@@ -185,7 +181,9 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
         nparts = clampi(ntile, 1, c->num_cu * 2);
         mode = kModeGram;
         const int NB = (n + 15) / 16;
-        if (NB == 2)
+        if (NB == 1)
+            gram_mfma_kernel<1><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
+        else if (NB == 2)
             gram_mfma_kernel<2><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
         else if (NB == 3)
             gram_mfma_kernel<3><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
@@ -213,13 +211,13 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
 }
 
 // Pass 3.  EMIT = false: X updated in place; EMIT = true: phi written to PHI.  CARRY (in-place,
-// n > 16 only): the update also leaves the Gram partials of the new X in c->partials.
+// the update also leaves the Gram partials of the new X in c->partials.
 template <bool EMIT, bool CARRY>
 int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, float eps,
                hipStream_t s)
 {
     KernelTimer t(c, SVGD_KERNEL_UPDATE, s);
-    if (n <= 16) {
+    if (n <= kValuMaxN) {
         const int64_t ngroups = (D + 3) / 4;
         // fewer, longer-lived workgroups when each one ends with a reduction of its pair sums
         const int per_cu = CARRY ? 4 : 8;
@@ -238,7 +236,9 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int NB = (n + 15) / 16;
         if (CARRY) c->carry_nparts = (grid - 1) * 4 + 1;
 #define UPD(NBV, FULL) update_mfma_kernel<NBV, EMIT, FULL, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps, c->partials)
-        if (n == 32) UPD(2, true);
+        if (n == 16) UPD(1, true);
+        else if (NB == 1) UPD(1, false);
+        else if (n == 32) UPD(2, true);
         else if (n == 48) UPD(3, true);
         else if (n == 64) UPD(4, true);
         else if (NB == 2) UPD(2, false);

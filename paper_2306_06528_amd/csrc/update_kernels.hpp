@@ -18,7 +18,7 @@
 namespace svgd {
 
 // ---------------------------------------------------------------------------------------------
-// n <= 16: vector ALU, lanes = columns, 4 consecutive columns per thread (16-byte loads, 1 KiB
+// n <= kValuMaxN (12): vector ALU, lanes = columns, 4 consecutive columns per thread (16-byte loads, 1 KiB
 // contiguous per row per wave).  C and rho are wave-uniform and read through scalar loads.
 // ---------------------------------------------------------------------------------------------
 template <int N, bool EMIT, bool CARRY>
@@ -40,8 +40,14 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
         for (int p = 0; p < P; ++p) pacc[p] = 0.f;
     }
     const float c2h = st->two_over_h;
-    const float *__restrict__ C = coef + kOffC;
-    const float *__restrict__ rho = coef + kOffRho;
+    // C and rho are wave-uniform.  They are staged in LDS and read back as broadcasts: a chain of
+    // dependent scalar loads from global memory costs microseconds per wave, which is all there
+    // is to hide behind when D is small.
+    __shared__ __attribute__((aligned(16))) float C[N * N];
+    __shared__ float rho[N];
+    for (int e = threadIdx.x; e < N * N; e += 256) C[e] = coef[kOffC + e];
+    if (threadIdx.x < N) rho[threadIdx.x] = coef[kOffRho + threadIdx.x];
+    __syncthreads();
     const int64_t ngroups = (D + 3) >> 2;
     const int64_t nthreads = (int64_t)gridDim.x * 256;
     for (int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x; grp < ngroups; grp += nthreads) {
@@ -53,6 +59,7 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
             x[j] = load4(X + (int64_t)j * D, col, D, full);
             z[j] = load4_stream(G + (int64_t)j * D, col, D, full);
         }
+
         f32x4 m = f32x4{0.f, 0.f, 0.f, 0.f};
         if constexpr (CARRY && !kDiff) { // centre by the pre-update column mean
 #pragma unroll
@@ -107,7 +114,7 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 }
 
 // ---------------------------------------------------------------------------------------------
-// 16 < n <= 64: matrix cores, v_mfma_f32_16x16x4_f32 with M = output particle i, K = input
+// kValuMaxN < n <= 64: matrix cores, v_mfma_f32_16x16x4_f32 with M = output particle i, K = input
 // particle j, N = column.
 //
 // Register tile.  A wave owns 16*NB rows x 64 columns at a time: lane (q = lane/16, c = lane%16)
