@@ -9,12 +9,12 @@
 namespace svgd {
 
 // ---------------------------------------------------------------------------------------------
-// n <= kValuMaxN (12): vector ALU, lanes = columns.  Each thread loads 4 consecutive columns of every row
-// (one 16-byte load per row, 1 KiB contiguous per row per wave) and keeps one fp32 accumulator
-// per pair in registers.
+// n <= kValuMaxN (12): vector ALU, lanes = columns.  Each thread loads 4 consecutive columns of
+// every row (one 16-byte load per row, 1 KiB contiguous per row per wave) and keeps one fp32
+// accumulator per pair in registers.
 //   N <= 8 : direct differences (x_i - x_j)^2 - no cancellation at all.
 //   N  > 8 : Gram of the column-centred y = x - mean_i(x); d2 = S_ii + S_jj - 2 S_ij later.
-// Chains are short (D / (4 * threads) terms per accumulator); lanes are combined by shuffles,
+// Chains are short (D / (4 * threads) terms per accumulator); lanes are combined by DPP adds,
 // waves through LDS, workgroups in fp64 by the reduce kernel.
 // ---------------------------------------------------------------------------------------------
 template <int N>

@@ -18,8 +18,8 @@
 namespace svgd {
 
 // ---------------------------------------------------------------------------------------------
-// n <= kValuMaxN (12): vector ALU, lanes = columns, 4 consecutive columns per thread (16-byte loads, 1 KiB
-// contiguous per row per wave).  C and rho are wave-uniform and read through scalar loads.
+// n <= kValuMaxN (12): vector ALU, lanes = columns, 4 consecutive columns per thread (16-byte
+// loads, 1 KiB contiguous per row per wave).  C and rho are wave-uniform: LDS broadcasts.
 // ---------------------------------------------------------------------------------------------
 template <int N, bool EMIT, bool CARRY>
 __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
