@@ -49,8 +49,8 @@ def cpu_baseline(wl):
     import numpy as np
     from oracle import svgd_oracle
     n = wl.n
-    # the oracle costs O(n^2) per column: 4M columns at n=64 is 10-20 s on 8-16 threads
-    ds = int(min(wl.D, max(4096, 4_000_000 * 64 // max(n, 4))))
+    # the oracle costs O(n^2) per column: 12M columns at n=64 are about 100 core-seconds
+    ds = int(min(wl.D, max(4096, 12_000_000 * 64 // max(n, 4))))
     Xs = wl.X0[:, :ds].contiguous().cpu().numpy()
     Gs = wl.score(wl.X0, 0)[:, :ds].contiguous().cpu().numpy()
     t0 = time.perf_counter()
