@@ -226,7 +226,8 @@ def main():
         "separate_gram": alt,
         "gram_gbs": gram_gbs,
         "roofline": {
-            "kernel": "update_mfma_kernel (fused K.[G|X] in-place update" +
+            "kernel": ("update_valu_kernel" if n <= 12 else "update_mfma_kernel") +
+                      " (fused K.[G|X] in-place update" +
                       (", also accumulating the next step's pair sums)" if carry else ")"),
             "bound": "hbm",
             "achieved": upd_gbs,

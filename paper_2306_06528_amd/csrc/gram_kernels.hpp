@@ -17,11 +17,54 @@ namespace svgd {
 // Chains are short (D / (4 * threads) terms per accumulator); lanes are combined by DPP adds,
 // waves through LDS, workgroups in fp64 by the reduce kernel.
 // ---------------------------------------------------------------------------------------------
+
+// One 4-column group's contribution to every pair sum: acc[tri(i, j, N)] += sum over the 4
+// columns of (x_i - x_j)^2 (N <= 8) or of y_i y_j, y = x - column mean (N > 8; x is overwritten
+// by y).
+template <int N>
+__device__ __forceinline__ void pair_accumulate(f32x4 (&x)[N], float (&acc)[N * (N + 1) / 2])
+{
+    constexpr bool kDiff = (N <= 8);
+    if constexpr (kDiff) {
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+#pragma unroll
+            for (int j = i + 1; j < N; ++j) {
+                const f32x4 d = x[i] - x[j];
+                float a = acc[tri(i, j, N)];
+                a = fmaf(d.x, d.x, a);
+                a = fmaf(d.y, d.y, a);
+                a = fmaf(d.z, d.z, a);
+                a = fmaf(d.w, d.w, a);
+                acc[tri(i, j, N)] = a;
+            }
+        }
+    } else {
+        f32x4 m = x[0];
+#pragma unroll
+        for (int j = 1; j < N; ++j) m += x[j];
+        m *= (1.0f / N);
+#pragma unroll
+        for (int j = 0; j < N; ++j) x[j] -= m; // columns beyond D were loaded as 0 -> stay 0
+#pragma unroll
+        for (int i = 0; i < N; ++i) {
+#pragma unroll
+            for (int j = i; j < N; ++j) {
+                float a = acc[tri(i, j, N)];
+                a = fmaf(x[i].x, x[j].x, a);
+                a = fmaf(x[i].y, x[j].y, a);
+                a = fmaf(x[i].z, x[j].z, a);
+                a = fmaf(x[i].w, x[j].w, a);
+                acc[tri(i, j, N)] = a;
+            }
+        }
+    }
+}
+
 template <int N>
 __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict__ X, int64_t D,
                                                         float *__restrict__ partials)
 {
-    constexpr bool kDiff = (N <= 8);
     constexpr int P = N * (N + 1) / 2;
     float acc[P];
 #pragma unroll
@@ -29,42 +72,6 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
 
     const int64_t ngroups = (D + 3) >> 2;
     const int64_t nthreads = (int64_t)gridDim.x * 256;
-    auto accumulate = [&](f32x4 (&x)[N]) __attribute__((always_inline)) {
-        if constexpr (kDiff) {
-#pragma unroll
-            for (int i = 0; i < N; ++i) {
-#pragma unroll
-                for (int j = i + 1; j < N; ++j) {
-                    const f32x4 d = x[i] - x[j];
-                    float a = acc[tri(i, j, N)];
-                    a = fmaf(d.x, d.x, a);
-                    a = fmaf(d.y, d.y, a);
-                    a = fmaf(d.z, d.z, a);
-                    a = fmaf(d.w, d.w, a);
-                    acc[tri(i, j, N)] = a;
-                }
-            }
-        } else {
-            f32x4 m = x[0];
-#pragma unroll
-            for (int j = 1; j < N; ++j) m += x[j];
-            m *= (1.0f / N);
-#pragma unroll
-            for (int j = 0; j < N; ++j) x[j] -= m; // columns beyond D were loaded as 0 -> stay 0
-#pragma unroll
-            for (int i = 0; i < N; ++i) {
-#pragma unroll
-                for (int j = i; j < N; ++j) {
-                    float a = acc[tri(i, j, N)];
-                    a = fmaf(x[i].x, x[j].x, a);
-                    a = fmaf(x[i].y, x[j].y, a);
-                    a = fmaf(x[i].z, x[j].z, a);
-                    a = fmaf(x[i].w, x[j].w, a);
-                    acc[tri(i, j, N)] = a;
-                }
-            }
-        }
-    };
     // two column groups per iteration when the registers allow: twice the loads in flight
     constexpr int U = (N <= 8) ? 2 : 1;
     for (int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x; grp < ngroups; grp += U * nthreads) {
@@ -77,7 +84,7 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
             for (int j = 0; j < N; ++j) x[u][j] = load4(X + (int64_t)j * D, col, D, full);
         }
 #pragma unroll
-        for (int u = 0; u < U; ++u) accumulate(x[u]);
+        for (int u = 0; u < U; ++u) pair_accumulate<N>(x[u], acc);
     }
 
     __shared__ float red[4][P];

@@ -12,6 +12,7 @@
 #include "common.hpp"
 #include "gram_kernels.hpp"
 #include "swag_kernels.hpp"
+#include "tiny_kernels.hpp"
 #include "update_kernels.hpp"
 
 using namespace svgd;
@@ -193,7 +194,9 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
 
-    {
+    // few partials of few pairs: the bandwidth kernel sums them itself
+    const bool direct = P <= kBwThreads && (int64_t)nparts * P <= kDirectMaxFloats;
+    if (!direct) {
         KernelTimer t(c, SVGD_KERNEL_REDUCE, s);
         reduce_partials_kernel<<<dim3((P + 255) / 256, kSlices), 256, 0, s>>>(c->partials, nparts, P,
                                                                              c->part2);
@@ -202,7 +205,8 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
     if (e != hipSuccess) return fail(c, e);
     {
         KernelTimer t(c, SVGD_KERNEL_BANDWIDTH, s);
-        bandwidth_kernel<<<1, kBwThreads, 0, s>>>(c->part2, n, mode, c->h_fixed, c->state, c->coef);
+        bandwidth_kernel<<<1, kBwThreads, 0, s>>>(c->part2, direct ? c->partials : nullptr, nparts, n,
+                                                  mode, c->h_fixed, c->state, c->coef);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
@@ -220,7 +224,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
     if (n <= kValuMaxN) {
         const int64_t ngroups = (D + 3) / 4;
         // fewer, longer-lived workgroups when each one ends with a reduction of its pair sums
-        const int per_cu = CARRY ? 4 : 8;
+        const int per_cu = CARRY ? 2 : 8;
         const int grid = clampi((ngroups + 255) / 256, 1, c->num_cu * per_cu < kMaxParts ? c->num_cu * per_cu : kMaxParts);
         if (CARRY) c->carry_nparts = grid;
 #define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, eps, c->partials, grid, s)
@@ -231,10 +235,10 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int64_t nfull = D / 64;
         // one worker workgroup per CU: the kernel overlaps its own loads with its multiplies, and
         // fewer concurrent row streams keep more HBM pages open
-        const int max_workers = c->num_cu < (kMaxParts - 1) / 4 ? c->num_cu : (kMaxParts - 1) / 4;
+        const int max_workers = c->num_cu < kMaxParts - 1 ? c->num_cu : kMaxParts - 1;
         const int grid = clampi((nfull + 3) / 4, 1, max_workers) + 1;
         const int NB = (n + 15) / 16;
-        if (CARRY) c->carry_nparts = (grid - 1) * 4 + 1;
+        if (CARRY) c->carry_nparts = grid; // one partial per workgroup, the tail's included
 #define UPD(NBV, FULL) update_mfma_kernel<NBV, EMIT, FULL, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps, c->partials)
         if (n == 16) UPD(1, true);
         else if (NB == 1) UPD(1, false);
@@ -248,6 +252,34 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
+    return SVGD_OK;
+}
+
+// The single-launch path: sizes at which one workgroup does the whole step faster than three
+// dependent launches.  It neither reads nor leaves carried pair sums.
+bool is_tiny(int n, int64_t D) { return n <= kTinyMaxN && (int64_t)n * D <= kTinyMaxElems; }
+
+template <int WHAT>
+int run_tiny(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, float eps, hipStream_t s)
+{
+    {
+        KernelTimer t(c, WHAT == kTinyBandwidth ? SVGD_KERNEL_BANDWIDTH : SVGD_KERNEL_UPDATE, s);
+#define TINY(N) step_tiny_kernel<N, WHAT><<<1, kTinyThreads, 0, s>>>(X, G, PHI, D, eps, c->h_fixed, c->state, c->coef)
+        switch (n) {
+        case 1: TINY(1); break;
+        case 2: TINY(2); break;
+        case 3: TINY(3); break;
+        case 4: TINY(4); break;
+        case 5: TINY(5); break;
+        case 6: TINY(6); break;
+        case 7: TINY(7); break;
+        default: TINY(8); break;
+        }
+#undef TINY
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, e);
+    c->last_n = n;
     return SVGD_OK;
 }
 
@@ -356,8 +388,12 @@ int svgd_bandwidth(svgd_handle_t c, const float *X, int n, int64_t D, double *h_
     if (rc) return rc;
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
-    c->carry_valid = false; // the partials buffer is about to be overwritten
-    rc = run_kernel_matrix(c, X, n, D, s, false);
+    if (is_tiny(n, D)) {
+        rc = run_tiny<kTinyBandwidth>(c, const_cast<float *>(X), nullptr, nullptr, n, D, 0.f, s);
+    } else {
+        c->carry_valid = false; // the partials buffer is about to be overwritten
+        rc = run_kernel_matrix(c, X, n, D, s, false);
+    }
     if (rc) return rc;
     if (h_out_host) {
         hipError_t e = hipMemcpyAsync(h_out_host, &c->state->h, sizeof(double), hipMemcpyDeviceToHost, s);
@@ -380,6 +416,7 @@ int svgd_step(svgd_handle_t c, float *X, const float *G, int n, int64_t D, float
     const bool carry_mode = (c->flags & SVGD_FLAG_CARRY_GRAM) != 0;
     const bool use_carry = carry_mode && c->carry_valid && c->carry_X == X && c->carry_n == n && c->carry_D == D;
     c->carry_valid = false;
+    if (is_tiny(n, D)) return run_tiny<kTinyStep>(c, X, G, nullptr, n, D, eps, s);
     rc = run_kernel_matrix(c, X, n, D, s, use_carry);
     if (rc) return rc;
     if (!carry_mode) return run_update<false, false>(c, X, G, nullptr, n, D, eps, s);
@@ -402,6 +439,7 @@ int svgd_phi(svgd_handle_t c, const float *X, const float *G, int n, int64_t D, 
     if (overlaps(X, PHI, n, D) || overlaps(G, PHI, n, D)) return SVGD_ERR_INVALID_ARG;
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
+    if (is_tiny(n, D)) return run_tiny<kTinyPhi>(c, const_cast<float *>(X), G, PHI, n, D, 0.f, s);
     c->carry_valid = false; // the partials buffer is about to be overwritten
     rc = run_kernel_matrix(c, X, n, D, s, false);
     if (rc) return rc;

@@ -199,8 +199,8 @@ __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 
 // CARRY: additionally accumulate the Gram of the UPDATED columns, centred by the pre-update column
 // mean (any per-column shift common to all particles leaves every d2 unchanged), and write one
-// partial per wave (+ one for the tail) to gram_out in the format of gram_mfma_kernel.  The next
-// step can then skip its own pass over X.
+// partial per workgroup (the last one is the tail's) to gram_out in the format of
+// gram_mfma_kernel.  The next step can then skip its own pass over X.
 //
 // Instruction mix.  One wave per SIMD has to keep the matrix pipe, the vector ALU, LDS and the
 // memory pipe busy at once, so the work of a tile is ordered as
@@ -232,7 +232,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         float *tail_out = nullptr;
         if constexpr (CARRY) {
             const int P = n * (n + 1) / 2;
-            tail_out = gram_out + (int64_t)(gridDim.x - 1) * 4 * P; // after the worker waves' partials
+            tail_out = gram_out + (int64_t)(gridDim.x - 1) * P; // after the workers' partials
             if ((nfull << 6) >= D)
                 for (int p = threadIdx.x; p < P; p += 256) tail_out[p] = 0.f;
         }
@@ -504,19 +504,34 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     }
 
     if constexpr (CARRY) {
-        // one partial per wave, upper triangle in tri(i, j) order (zeros if the range was empty)
+        // One partial per workgroup, upper triangle in tri(i, j) order (zeros if all four ranges
+        // were empty): the waves' sums meet in their staging areas, which are free by now, and
+        // wave p mod 4 adds up and writes block pair p.
+        static_assert(NPAIR * 4 * 64 <= kUpdCur + kUpdCarry, "the staging area holds a wave's Gram sums");
+#pragma unroll
+        for (int p = 0; p < NPAIR; ++p) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) cur[(p * 4 + r) * 64 + lane] = accg[p][r];
+        }
+        __syncthreads();
+        const float *all = lds + NB * NB * 64 * 4;
         const int P = n * (n + 1) / 2;
-        float *out = gram_out + w * P;
+        float *out = gram_out + (int64_t)blockIdx.x * P;
         int p = 0;
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
 #pragma unroll
             for (int b2 = b; b2 < NB; ++b2) {
+                if ((p & 3) == wave) {
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int i = 16 * b + 4 * q + r;
-                    const int j = 16 * b2 + c16;
-                    if (i <= j && j < n) out[tri(i, j, n)] = accg[p][r];
+                    for (int r = 0; r < 4; ++r) {
+                        const int i = 16 * b + 4 * q + r;
+                        const int j = 16 * b2 + c16;
+                        const int e = (p * 4 + r) * 64 + lane;
+                        const float v = (all[e] + all[(kUpdCur + kUpdCarry) + e]) +
+                                        (all[2 * (kUpdCur + kUpdCarry) + e] + all[3 * (kUpdCur + kUpdCarry) + e]);
+                        if (i <= j && j < n) out[tri(i, j, n)] = v;
+                    }
                 }
                 ++p;
             }

@@ -79,10 +79,45 @@ def _random_problem(n, D, seed, x_std=1.0, device="cuda"):
 
 # every particle count takes its own template instance / row masking: cover them all at one
 # ragged D, and a set of D around the tile sizes (4, 64, 128, 256 columns) at a few n.
+# D = 1531 puts n <= 8 on the single-launch path (n * D <= 16384), D = 20011 puts every n on the
+# multi-kernel path.
+@pytest.mark.parametrize("D", [1531, 20_011])
 @pytest.mark.parametrize("n", list(range(1, 18)) + [24, 31, 32, 33, 47, 48, 49, 63, 64])
-def test_every_particle_count(svgd, n):
-    X, G = _random_problem(n, 1531, 1000 + n)
+def test_every_particle_count(svgd, n, D):
+    X, G = _random_problem(n, D, 1000 + n + D)
     check_one_step(svgd, X, G, 0.01)
+
+
+@pytest.mark.parametrize("n,D", [(1, 16_384), (1, 16_385), (2, 8192), (2, 8193), (4, 4096), (4, 4097),
+                                 (5, 3276), (5, 3277), (7, 2340), (7, 2341), (8, 2048), (8, 2049),
+                                 (8, 1), (3, 2), (6, 7)])
+def test_single_launch_path_and_its_size_limit(svgd, n, D):
+    """Both sides of n * D = 16384, where the single-workgroup kernel hands over to the
+    multi-kernel path, and the smallest shapes."""
+    X, G = _random_problem(n, D, 17 * n + D)
+    if n > 1 and D < 4:
+        X = X * 3.0
+    check_one_step(svgd, X, G, 0.05)
+    check_one_step(svgd, X, G, 0.05, h_fixed=2.0)
+
+
+def test_single_launch_and_carried_sums_do_not_mix(svgd):
+    """A handle that carries pair sums is used on a large problem, then a tiny one, then the large
+    one again: the tiny step must not leave sums behind that the large one would take for its own."""
+    nL, DL = 8, 50_021
+    XL, GL = _random_problem(nL, DL, 5, x_std=0.3)
+    XT, GT = _random_problem(4, 1024, 6, x_std=0.3)
+    with svgd.Svgd(8, DL, flags=svgd.FLAG_CARRY_GRAM) as eng:
+        eng.step(XL, GL, 0.05)
+        for X, G, n in ((XT, GT, 4), (XL, GL, nL), (XT, GT, 4), (XT, GT, 4), (XL, GL, nL), (XL, GL, nL)):
+            Xh = X.cpu().numpy()
+            eng.step(X, G, 0.05)
+            h, K = eng.get_last(n)
+            ref = orc.step(Xh, G.cpu().numpy(), 0.05)
+            assert abs(h - ref["h"]) / ref["h"] <= TOL_H
+            assert np.abs(K - ref["K"]).max() <= TOL_K
+            err = np.abs(X.cpu().numpy() - ref["X_new"]).max() / np.abs(ref["X_new"]).max()
+            assert err <= 1e-6
 
 
 @pytest.mark.parametrize("n", [1, 2, 4, 8, 13, 16, 20, 32, 40, 64])
@@ -403,7 +438,7 @@ def test_buffers_with_odd_base_alignment(svgd, n, shift):
 
 
 @pytest.mark.parametrize("flags", [0, 1])
-@pytest.mark.parametrize("n,D", [(4, 1024), (32, 20_001)])
+@pytest.mark.parametrize("n,D", [(4, 1024), (8, 4099), (32, 20_001)])
 def test_step_can_be_captured_in_a_graph(svgd, n, D, flags):
     """svgd_step neither allocates nor synchronises, so a caller may capture it in a HIP graph.
     The graph is replayed several times with eager work and synchronisations in between, and
