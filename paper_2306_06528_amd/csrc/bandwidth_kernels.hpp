@@ -9,7 +9,7 @@
 namespace svgd {
 
 constexpr int kBwThreads = 1024;
-constexpr int kSlices = 32; // slices of the partial reduction (see reduce_partials_kernel)
+constexpr int kSlices = 8; // slices of the partial reduction (see reduce_partials_kernel)
 
 __device__ inline int pair_index(int i, int j, int n) { return i * n - (i * (i + 1)) / 2 + (j - i - 1); } // i < j
 

@@ -236,7 +236,17 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     const int slice = blockIdx.y, nslices = gridDim.y;
     if (p >= P) return;
     double s = 0.0;
-    for (int k = slice; k < nparts; k += nslices) s += (double)partials[(int64_t)k * P + p];
+    constexpr int U = 16; // loads in flight per thread
+    for (int k = slice; k < nparts; k += U * nslices) {
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { // unconditional loads (index clamped) issue together
+            const int ku = k + u * nslices;
+            v[u] = partials[(int64_t)(ku < nparts ? ku : nparts - 1) * P + p];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) s += (k + u * nslices < nparts) ? (double)v[u] : 0.0;
+    }
     part2[(int64_t)slice * P + p] = s;
 }
 
