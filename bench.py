@@ -25,11 +25,15 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
     # (config, carried Gram?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True): (4081995.9, 2803354.3),
-    (5, False): (4069151.3, 2795026.4),
+    (5, True): (4081267.5, 2797114.4),
+    (5, False): (4069645.0, 2795026.3),
+    (3, True): (250219.2, 250530.3),
+    (3, False): (250146.7, 250000.3),
+    (4, True): (369110.9, 357076.1),
+    (4, False): (365622.7, 355099.5),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "a6f03f7ebfda969c3f780657c197a452f11b344e73f85cc1a32a02964e2c2a70"
+TRAFFIC_SOURCE_SHA256 = "5a189b371f429f73ac09e263f83ef7c0dfc632e8f84ee30f04dfd9e834453f58"
 
 
 def kernel_source_hash():
@@ -198,6 +202,7 @@ def main():
     upd_gbs = UPDATE_BYTES_PER_PARAM * n * D / (upd_ms * 1e-3) / 1e9
     gram_gbs = 4 * n * D / (kern_ms["gram"] * 1e-3) / 1e9 if kern_ms["gram"] > 0 else None
 
+    tiny = n <= 8 and n * D <= 16384   # sizes the library runs as a single kernel
     traffic = None
     key = (args.config, carry)
     if key in TRAFFIC_COUNTERS and kernel_source_hash() == TRAFFIC_SOURCE_SHA256:
@@ -226,7 +231,8 @@ def main():
         "separate_gram": alt,
         "gram_gbs": gram_gbs,
         "roofline": {
-            "kernel": ("update_valu_kernel" if n <= 12 else "update_mfma_kernel") +
+            "kernel": "step_tiny_kernel (the whole step in one workgroup)" if tiny else
+                      ("update_valu_kernel" if n <= 12 else "update_mfma_kernel") +
                       " (fused K.[G|X] in-place update" +
                       (", also accumulating the next step's pair sums)" if carry else ")"),
             "bound": "hbm",

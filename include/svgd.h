@@ -112,6 +112,10 @@ int svgd_get_last(svgd_handle_t h, double *h_out, float *K_host, void *stream);
  * on.  svgd_profile_end waits for those events and fills ms_sum[k] / count[k] (HOST arrays of
  * SVGD_KERNEL_KINDS entries) with the total elapsed milliseconds and the number of launches of
  * kernel kind k, then switches recording off.  At most 8192 launches are recorded per session.
+ * Not every kind runs in every step: a short list of partial sums is reduced inside the
+ * BANDWIDTH kernel (no REDUCE launch), carried pair sums replace the GRAM pass, and problems with
+ * n <= 8 and n * D <= 16384 run as one kernel, which is counted as UPDATE (as BANDWIDTH when
+ * svgd_bandwidth launches it).
  */
 enum svgd_kernel_kind {
     SVGD_KERNEL_GRAM = 0,      /* pairwise-d2 partial sums (pass over X) */
