@@ -134,7 +134,7 @@ def main():
                     help="also launch the plain copy kernel once over G (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); "
+        print("bench.py: this library runs on exactly one GPU (no sharding, no collectives); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
