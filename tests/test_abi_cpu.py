@@ -81,3 +81,18 @@ def test_binding_has_the_same_names():
     import paper_2306_06528_amd.svgd as b
     for m in ("step", "bandwidth", "phi", "get_last", "set_bandwidth", "close"):
         assert hasattr(b.Svgd, m)
+
+
+@pytest.mark.parametrize("compiler,std,suffix", [("gcc", "-std=c99", ".c"), ("g++", "-std=c++11", ".cpp")])
+def test_header_is_plain_c_and_cpp(tmp_path, compiler, std, suffix):
+    """The boundary is usable from C as well as C++: no torch or HIP types, nothing but <stdint.h>."""
+    import shutil
+    import subprocess
+    if shutil.which(compiler) is None:
+        pytest.skip(f"{compiler} not installed")
+    src = tmp_path / ("use_header" + suffix)
+    src.write_text('#include "svgd.h"\n'
+                   "int main(void) { svgd_handle_t h = 0; (void)h; return SVGD_OK + SVGD_MAX_PARTICLES * 0; }\n")
+    r = subprocess.run([compiler, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
