@@ -325,6 +325,51 @@ def test_config5_large_ensemble_full_size(svgd):
     _full_size_check(svgd, 5)
 
 
+@pytest.mark.parametrize("n,D,carry", [(3, 800_000_001, True), (16, 150_000_001, False), (64, 34_000_001, True)])
+def test_more_than_2_to_31_elements(svgd, n, D, carry):
+    """n * D = 2.4e9 elements (9.6 GB per array): element offsets beyond 32 bits on the vector-ALU
+    and on the matrix-core path.  h and K against the oracle's full pass; phi and the in-place
+    update on column chunks at both ends and around element offset 2^31."""
+    assert n * D > 2 ** 31
+    chunk = 4096
+    g = torch.Generator(device="cuda")
+    g.manual_seed(5 * n + 1)
+    X = torch.randn(n, D, generator=g, device="cuda") * 0.02
+    G = torch.randn(n, D, generator=g, device="cuda") * 1e-3
+    eps = 1e-3
+    cross = (2 ** 31) % D   # a column at which some row's element offset passes 2^31
+    starts = sorted({0, D - chunk, min(max(cross - chunk // 2, 0), D - chunk), D // 2 + 7})
+    Xh = X.cpu().numpy()
+    G_chunks = {s0: G[:, s0:s0 + chunk].cpu().numpy() for s0 in starts}
+    PHI = torch.empty_like(X)
+    with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM if carry else 0) as eng:
+        eng.phi(X, G, PHI)
+        h, K = eng.get_last(n)
+        eng.step(X, G, eps)
+        torch.cuda.synchronize()
+        d2 = orc.pairwise_d2(Xh)
+        h_ref = orc.bandwidth(d2)
+        K_ref, _ = orc.kernel(d2, h_ref)
+        assert abs(h - h_ref) / h_ref <= TOL_H, f"h {h} vs {h_ref}"
+        assert np.abs(K - K_ref).max() <= TOL_K
+        scale = float(PHI.abs().max().item())
+        for s0 in starts:
+            # phi_cols reads whole rows of X and G: give it G rows that are right on this chunk
+            ref = orc.phi_cols(Xh[:, s0:s0 + chunk], G_chunks[s0], K_ref, h_ref, 0, chunk)
+            got = PHI[:, s0:s0 + chunk].cpu().numpy().astype(np.float64)
+            assert np.abs(got - ref).max() / scale <= TOL_PHI, f"chunk at {s0}"
+            want = Xh[:, s0:s0 + chunk].astype(np.float64) + np.float64(np.float32(eps)) * got
+            assert _ulp_diff(want, X[:, s0:s0 + chunk].cpu().numpy()) <= 1.0, f"chunk at {s0}"
+        if carry:   # the next step takes its pair sums from the update that just ran
+            X1h = X.cpu().numpy()
+            eng.step(X, G, eps)
+            h2, K2 = eng.get_last(n)
+            d2 = orc.pairwise_d2(X1h)
+            h2_ref = orc.bandwidth(d2)
+            assert abs(h2 - h2_ref) / h2_ref <= TOL_H
+            assert np.abs(K2 - orc.kernel(d2, h2_ref)[0]).max() <= TOL_K
+
+
 # ----------------------------------------------------------------------------------------------
 # carried Gram (SVGD_FLAG_CARRY_GRAM): step t's update also accumulates the pair sums of the new
 # X, and step t+1 skips its own pass over X
