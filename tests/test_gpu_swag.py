@@ -73,3 +73,28 @@ def test_full_size_resnet18_particles(svgd):
     em = np.abs(mean[:, tcols].cpu().numpy() - mean_ref).max() / np.abs(mean_ref).max()
     es = np.abs(sq[:, tcols].cpu().numpy() - sq_ref).max() / np.abs(sq_ref).max()
     assert em <= TOL and es <= TOL, (em, es)
+
+
+def test_more_than_2_to_31_elements(svgd):
+    """n * D = 2.4e9 parameters: flat indices beyond 32 bits; checked on column ranges at both
+    ends and around flat index 2^31."""
+    n, D = 3, 800_000_001
+    assert n * D > 2 ** 31
+    g = torch.Generator(device="cuda")
+    g.manual_seed(9)
+    mean = torch.empty(n, D, device="cuda")
+    sq = torch.empty(n, D, device="cuda")
+    cross = (2 ** 31) % D
+    cols = np.concatenate([np.arange(0, 4096), np.arange(D - 4096, D), np.arange(cross - 2048, cross + 2048)])
+    tcols = torch.from_numpy(cols).cuda()
+    mean_ref = np.zeros((n, cols.size))
+    sq_ref = np.zeros((n, cols.size))
+    X = torch.empty(n, D, device="cuda")
+    for t in range(2):
+        X.normal_(0.0, 0.02, generator=g)
+        svgd.swag_update_moments(mean, sq, X, t)
+        orc.swag_update(mean_ref, sq_ref, X[:, tcols].contiguous().cpu().numpy(), t)
+    torch.cuda.synchronize()
+    em = np.abs(mean[:, tcols].cpu().numpy() - mean_ref).max() / np.abs(mean_ref).max()
+    es = np.abs(sq[:, tcols].cpu().numpy() - sq_ref).max() / np.abs(sq_ref).max()
+    assert em <= TOL and es <= TOL, (em, es)
