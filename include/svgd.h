@@ -22,7 +22,8 @@
  *     enqueued on it; calls return before the work completes unless stated otherwise.
  *   - The caller owns X, G, PHI.  The handle owns its scratch (partial sums, K, h), allocated
  *     once in svgd_create and freed in svgd_destroy; svgd_step/svgd_phi/svgd_bandwidth never
- *     allocate.  One handle must not be used from two streams at once.
+ *     allocate.  One handle must not be used from two streams or two host threads at once
+ *     (different handles are independent).
  *   - Return value: SVGD_OK (0) or a negative svgd_status.  No entry point aborts or throws.
  *     Non-finite DATA is not checked and propagates as IEEE NaN/Inf.
  */
