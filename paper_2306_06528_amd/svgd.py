@@ -103,10 +103,19 @@ class Svgd:
 
     def __init__(self, max_n: int, max_D: int, device: int = -1, flags: int = 0):
         self._h = _H()
+        self._last_n = 0
         rc = _lib.svgd_create(ctypes.byref(self._h), int(max_n), int(max_D), int(device), int(flags))
         if rc != SVGD_OK:
             self._h = _H()
             raise SvgdError(rc)
+        self._device = int(device) if device >= 0 else torch.cuda.current_device()
+
+    def _mat(self, t, name):
+        """A matrix argument: also on the handle's device (a pointer of another GPU would fault)."""
+        t = _dev_matrix(t, name)
+        if t.get_device() != self._device:
+            raise ValueError(f"{name} is on cuda:{t.get_device()}, the handle on cuda:{self._device}")
+        return t
 
     def _check(self, rc):
         if rc != SVGD_OK:
@@ -119,32 +128,38 @@ class Svgd:
         self._check(_lib.svgd_forget_carry(self._h))
 
     def bandwidth(self, X, want_h=True, stream=None):
-        X = _dev_matrix(X, "X")
+        X = self._mat(X, "X")
         n, D = X.shape
         out = ctypes.c_double(0.0)
         self._check(_lib.svgd_bandwidth(self._h, X.data_ptr(), n, D,
                                         ctypes.byref(out) if want_h else None, _stream_ptr(stream)))
+        self._last_n = n
         return out.value if want_h else None
 
     def step(self, X, G, eps: float, stream=None):
-        X, G = _dev_matrix(X, "X"), _dev_matrix(G, "G")
+        X, G = self._mat(X, "X"), self._mat(G, "G")
         if X.shape != G.shape:
             raise ValueError("X and G must have the same shape")
         n, D = X.shape
         self._check(_lib.svgd_step(self._h, X.data_ptr(), G.data_ptr(), n, D, float(eps),
                                    _stream_ptr(stream)))
+        self._last_n = n
 
     def phi(self, X, G, PHI, stream=None):
-        X, G, PHI = _dev_matrix(X, "X"), _dev_matrix(G, "G"), _dev_matrix(PHI, "PHI")
+        X, G, PHI = self._mat(X, "X"), self._mat(G, "G"), self._mat(PHI, "PHI")
         if X.shape != G.shape or X.shape != PHI.shape:
             raise ValueError("X, G and PHI must have the same shape")
         n, D = X.shape
         self._check(_lib.svgd_phi(self._h, X.data_ptr(), G.data_ptr(), n, D, PHI.data_ptr(),
                                   _stream_ptr(stream)))
+        self._last_n = n
 
     def get_last(self, n: int, stream=None):
-        """(h, K) of the most recent call; K is an (n, n) float32 numpy array."""
+        """(h, K) of the most recent call; K is an (n, n) float32 numpy array.  n must be that
+        call's particle count: the library copies exactly that many rows and columns."""
         import numpy as np
+        if n != self._last_n:
+            raise ValueError(f"the last call had n = {self._last_n}, not {n}")
         K = np.empty((n, n), np.float32)
         h = ctypes.c_double(0.0)
         self._check(_lib.svgd_get_last(self._h, ctypes.byref(h), K.ctypes.data_as(ctypes.c_void_p),

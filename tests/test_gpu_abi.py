@@ -56,6 +56,14 @@ def test_binding_raises(mod):
         eng.step(X, torch.randn_like(X), 0.1)
     with pytest.raises(TypeError):
         eng.step(X.cpu(), X.cpu(), 0.1)
+    with pytest.raises(ValueError):          # nothing computed yet
+        eng.get_last(4)
+    Y = torch.randn(3, 100, device="cuda")
+    eng.step(Y, torch.randn_like(Y), 0.1)
+    with pytest.raises(ValueError):          # K of the last call is 3 x 3: no room to get that wrong
+        eng.get_last(2)
+    h, K = eng.get_last(3)
+    assert h > 0 and K.shape == (3, 3)
     eng.close()
     with pytest.raises(mod.SvgdError):
         mod.Svgd(65, 100)
