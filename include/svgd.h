@@ -102,8 +102,9 @@ int svgd_phi(svgd_handle_t h, const float *X, const float *G, int n, int64_t D, 
 
 /*
  * Copy the bandwidth and kernel matrix of the most recent svgd_bandwidth/svgd_step/svgd_phi call
- * to HOST memory: *h_out (nullable) receives h; K_host (nullable, n*n floats, row-major)
- * receives K.  Synchronises `stream` first.  INVALID_ARG if no step has run yet.
+ * to HOST memory: *h_out (nullable) receives h; K_host (nullable, row-major) receives K and must
+ * have room for n*n floats with the n of that call - the library copies exactly that many and
+ * cannot check the buffer.  Synchronises `stream` first.  INVALID_ARG if no step has run yet.
  */
 int svgd_get_last(svgd_handle_t h, double *h_out, float *K_host, void *stream);
 
