@@ -181,32 +181,39 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
     const int P = n * (n + 1) / 2;
 
     if (partials != nullptr) {
-        // PW = P rounded up to a power of two; thread (kk, pp) = (tid / PW, tid % PW) sums the
-        // partials kk, kk + KL, ... of entry pp, many loads in flight at a time; the KL lane sums
-        // of an entry meet in LDS (sh.pr is not in use yet).
-        int PW = 64;
-        while (PW < P) PW <<= 1;
-        const int KL = kBwThreads / PW;
-        const int pp = tid & (PW - 1), kk = tid / PW;
+        // Thread tid = kk * P + pp (kk < KL <= threads / P) sums the partials kk, kk + KL, ... of
+        // entry pp: consecutive threads read consecutive floats, 16 loads in flight each; the KL
+        // sums of an entry meet in LDS (sh.pr is not in use yet).
+        const int KL = kBwThreads / P < 32 ? kBwThreads / P : 32; // capped: the KL sums are added serially
+        const int kk = tid / P, pp = tid - kk * P;
         double s = 0.0;
-        if (pp < P) {
-            constexpr int U = 32; // loads in flight per thread
-            for (int k = kk; k < nparts; k += U * KL) {
+        if (kk < KL) {
+            constexpr int U = 16;
+            const float *src = partials + tid; // element (kk, pp); partial k + KL is KL * P floats on
+            const int64_t stride = (int64_t)KL * P;
+            int k = kk;
+            for (; k + (U - 1) * KL < nparts; k += U * KL) {
                 float v[U];
 #pragma unroll
-                for (int u = 0; u < U; ++u) { // unconditional loads (index clamped) issue together
-                    const int ku = k + u * KL;
-                    v[u] = partials[(int64_t)(ku < nparts ? ku : nparts - 1) * P + pp];
-                }
+                for (int u = 0; u < U; ++u) v[u] = src[(int64_t)u * stride];
 #pragma unroll
-                for (int u = 0; u < U; ++u) s += (k + u * KL < nparts) ? (double)v[u] : 0.0;
+                for (int u = 0; u < U; ++u) s += (double)v[u];
+                src += U * stride;
+            }
+            if (k < nparts) { // the last, partly filled batch: loads clamped to the last partial
+                float v[U];
+                const int left = (nparts - 1 - k) / KL; // index of the last valid load
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] = src[(int64_t)(u < left ? u : left) * stride];
+#pragma unroll
+                for (int u = 0; u < U; ++u) s += (u <= left) ? (double)v[u] : 0.0;
             }
         }
         sh.pr[tid] = s;
         __syncthreads();
         if (tid < P) {
             double t = 0.0;
-            for (int q = 0; q < KL; ++q) t += sh.pr[q * PW + tid];
+            for (int q = 0; q < KL; ++q) t += sh.pr[q * P + tid];
             sh.S[tid] = t;
         }
     } else {
