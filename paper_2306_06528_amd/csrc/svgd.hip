@@ -37,6 +37,7 @@ struct svgd_ctx {
     const float *carry_X;
     int carry_n;
     int64_t carry_D;
+    int64_t carry_ld;
     int carry_nparts;
     int last_n; // 0 = nothing computed yet
     int last_hip_error;
@@ -114,31 +115,32 @@ struct KernelTimer {
     }
 };
 
-int check_shape(svgd_ctx *c, int n, int64_t D)
+int check_shape(svgd_ctx *c, int n, int64_t D, int64_t ld)
 {
-    if (n < 1 || D < 1) return SVGD_ERR_INVALID_ARG;
+    if (n < 1 || D < 1 || ld < D) return SVGD_ERR_INVALID_ARG;
     if (n > c->max_n || D > c->max_D) return SVGD_ERR_TOO_LARGE;
     return SVGD_OK;
 }
 
-bool overlaps(const float *a, const float *b, int n, int64_t D)
+// n rows of D floats, ld floats apart: the byte ranges from the first to the last element
+bool overlaps(const float *a, const float *b, int n, int64_t D, int64_t ld)
 {
-    const uintptr_t bytes = (uintptr_t)n * (uintptr_t)D * sizeof(float);
+    const uintptr_t bytes = ((uintptr_t)(n - 1) * (uintptr_t)ld + (uintptr_t)D) * sizeof(float);
     const uintptr_t pa = (uintptr_t)a, pb = (uintptr_t)b;
     return pa < pb + bytes && pb < pa + bytes;
 }
 
 template <int N>
-void launch_gram_valu(const float *X, int64_t D, float *partials, int grid, hipStream_t s)
+void launch_gram_valu(const float *X, int64_t D, int64_t ld, float *partials, int grid, hipStream_t s)
 {
-    gram_valu_kernel<N><<<grid, 256, 0, s>>>(X, D, partials);
+    gram_valu_kernel<N><<<grid, 256, 0, s>>>(X, D, ld, partials);
 }
 
 template <int N, bool EMIT, bool CARRY>
 void launch_update_valu(float *X, const float *G, float *PHI, const float *coef, const DevState *st,
-                        int64_t D, float eps, float *gram_out, int grid, hipStream_t s)
+                        int64_t D, int64_t ld, float eps, float *gram_out, int grid, hipStream_t s)
 {
-    update_valu_kernel<N, EMIT, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, eps, gram_out);
+    update_valu_kernel<N, EMIT, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out);
 }
 
 #define SVGD_SWITCH_N(n, CALL)                                                                     \
@@ -161,7 +163,7 @@ int clampi(int64_t v, int lo, int hi) { return (int)(v < lo ? lo : (v > hi ? hi 
 
 // Passes 1 and 2: Gram partials -> fp64 reduction -> h, K, coefficient tables (all on `s`).
 // With use_carry the partials the previous update left in c->partials stand in for pass 1.
-int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t s, bool use_carry)
+int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld, hipStream_t s, bool use_carry)
 {
     const int P = n * (n + 1) / 2;
     int nparts, mode;
@@ -173,7 +175,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
         nparts = clampi((ngroups + 255) / 256, 1, c->num_cu * 3); // all resident at once; each ends with a reduction
         mode = (n <= 8) ? kModeDiff : kModeGram;
         KernelTimer t(c, SVGD_KERNEL_GRAM, s);
-#define CALL(N) launch_gram_valu<N>(X, D, c->partials, nparts, s)
+#define CALL(N) launch_gram_valu<N>(X, D, ld, c->partials, nparts, s)
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
     } else {
@@ -183,13 +185,13 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
         mode = kModeGram;
         const int NB = (n + 15) / 16;
         if (NB == 1)
-            gram_mfma_kernel<1><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
+            gram_mfma_kernel<1><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials);
         else if (NB == 2)
-            gram_mfma_kernel<2><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
+            gram_mfma_kernel<2><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials);
         else if (NB == 3)
-            gram_mfma_kernel<3><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
+            gram_mfma_kernel<3><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials);
         else
-            gram_mfma_kernel<4><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, c->partials);
+            gram_mfma_kernel<4><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials);
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
@@ -217,7 +219,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, hipStream_t
 // Pass 3.  EMIT = false: X updated in place; EMIT = true: phi written to PHI.  CARRY (in-place,
 // the update also leaves the Gram partials of the new X in c->partials.
 template <bool EMIT, bool CARRY>
-int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, float eps,
+int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, int64_t ld, float eps,
                hipStream_t s)
 {
     KernelTimer t(c, SVGD_KERNEL_UPDATE, s);
@@ -227,7 +229,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int per_cu = CARRY ? 2 : 8;
         const int grid = clampi((ngroups + 255) / 256, 1, c->num_cu * per_cu < kMaxParts ? c->num_cu * per_cu : kMaxParts);
         if (CARRY) c->carry_nparts = grid;
-#define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, eps, c->partials, grid, s)
+#define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, ld, eps, c->partials, grid, s)
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
     } else {
@@ -239,7 +241,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int grid = clampi((nfull + 3) / 4, 1, max_workers) + 1;
         const int NB = (n + 15) / 16;
         if (CARRY) c->carry_nparts = grid; // one partial per workgroup, the tail's included
-#define UPD(NBV, FULL) update_mfma_kernel<NBV, EMIT, FULL, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, eps, c->partials)
+#define UPD(NBV, FULL) update_mfma_kernel<NBV, EMIT, FULL, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials)
         if (n == 16) UPD(1, true);
         else if (NB == 1) UPD(1, false);
         else if (n == 32) UPD(2, true);
@@ -260,11 +262,11 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
 bool is_tiny(int n, int64_t D) { return n <= kTinyMaxN && (int64_t)n * D <= kTinyMaxElems; }
 
 template <int WHAT>
-int run_tiny(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, float eps, hipStream_t s)
+int run_tiny(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, int64_t ld, float eps, hipStream_t s)
 {
     {
         KernelTimer t(c, WHAT == kTinyBandwidth ? SVGD_KERNEL_BANDWIDTH : SVGD_KERNEL_UPDATE, s);
-#define TINY(N) step_tiny_kernel<N, WHAT><<<1, kTinyThreads, 0, s>>>(X, G, PHI, D, eps, c->h_fixed, c->state, c->coef)
+#define TINY(N) step_tiny_kernel<N, WHAT><<<1, kTinyThreads, 0, s>>>(X, G, PHI, D, ld, eps, c->h_fixed, c->state, c->coef)
         switch (n) {
         case 1: TINY(1); break;
         case 2: TINY(2); break;
@@ -314,6 +316,7 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
     c->carry_X = nullptr;
     c->carry_n = 0;
     c->carry_D = 0;
+    c->carry_ld = 0;
     c->carry_nparts = 0;
     c->last_n = 0;
     c->last_hip_error = 0;
@@ -379,20 +382,21 @@ int svgd_forget_carry(svgd_handle_t c)
     return SVGD_OK;
 }
 
-int svgd_bandwidth(svgd_handle_t c, const float *X, int n, int64_t D, double *h_out_host, void *stream)
+int svgd_bandwidth_ld(svgd_handle_t c, const float *X, int n, int64_t D, int64_t ld, double *h_out_host,
+                      void *stream)
 {
     int rc = check_handle(c);
     if (rc) return rc;
     if (!X) return SVGD_ERR_INVALID_ARG;
-    rc = check_shape(c, n, D);
+    rc = check_shape(c, n, D, ld);
     if (rc) return rc;
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
     if (is_tiny(n, D)) {
-        rc = run_tiny<kTinyBandwidth>(c, const_cast<float *>(X), nullptr, nullptr, n, D, 0.f, s);
+        rc = run_tiny<kTinyBandwidth>(c, const_cast<float *>(X), nullptr, nullptr, n, D, ld, 0.f, s);
     } else {
         c->carry_valid = false; // the partials buffer is about to be overwritten
-        rc = run_kernel_matrix(c, X, n, D, s, false);
+        rc = run_kernel_matrix(c, X, n, D, ld, s, false);
     }
     if (rc) return rc;
     if (h_out_host) {
@@ -403,47 +407,66 @@ int svgd_bandwidth(svgd_handle_t c, const float *X, int n, int64_t D, double *h_
     return SVGD_OK;
 }
 
-int svgd_step(svgd_handle_t c, float *X, const float *G, int n, int64_t D, float eps, void *stream)
+int svgd_bandwidth(svgd_handle_t c, const float *X, int n, int64_t D, double *h_out_host, void *stream)
+{
+    return svgd_bandwidth_ld(c, X, n, D, D, h_out_host, stream);
+}
+
+int svgd_step_ld(svgd_handle_t c, float *X, const float *G, int n, int64_t D, int64_t ld, float eps,
+                 void *stream)
 {
     int rc = check_handle(c);
     if (rc) return rc;
     if (!X || !G || !std::isfinite(eps)) return SVGD_ERR_INVALID_ARG;
-    rc = check_shape(c, n, D);
+    rc = check_shape(c, n, D, ld);
     if (rc) return rc;
-    if (overlaps(X, G, n, D)) return SVGD_ERR_INVALID_ARG;
+    if (overlaps(X, G, n, D, ld)) return SVGD_ERR_INVALID_ARG;
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
     const bool carry_mode = (c->flags & SVGD_FLAG_CARRY_GRAM) != 0;
-    const bool use_carry = carry_mode && c->carry_valid && c->carry_X == X && c->carry_n == n && c->carry_D == D;
+    const bool use_carry = carry_mode && c->carry_valid && c->carry_X == X && c->carry_n == n &&
+                           c->carry_D == D && c->carry_ld == ld;
     c->carry_valid = false;
-    if (is_tiny(n, D)) return run_tiny<kTinyStep>(c, X, G, nullptr, n, D, eps, s);
-    rc = run_kernel_matrix(c, X, n, D, s, use_carry);
+    if (is_tiny(n, D)) return run_tiny<kTinyStep>(c, X, G, nullptr, n, D, ld, eps, s);
+    rc = run_kernel_matrix(c, X, n, D, ld, s, use_carry);
     if (rc) return rc;
-    if (!carry_mode) return run_update<false, false>(c, X, G, nullptr, n, D, eps, s);
-    rc = run_update<false, true>(c, X, G, nullptr, n, D, eps, s);
+    if (!carry_mode) return run_update<false, false>(c, X, G, nullptr, n, D, ld, eps, s);
+    rc = run_update<false, true>(c, X, G, nullptr, n, D, ld, eps, s);
     if (rc) return rc;
     c->carry_valid = true;
     c->carry_X = X;
     c->carry_n = n;
     c->carry_D = D;
+    c->carry_ld = ld;
     return SVGD_OK;
 }
 
-int svgd_phi(svgd_handle_t c, const float *X, const float *G, int n, int64_t D, float *PHI, void *stream)
+int svgd_step(svgd_handle_t c, float *X, const float *G, int n, int64_t D, float eps, void *stream)
+{
+    return svgd_step_ld(c, X, G, n, D, D, eps, stream);
+}
+
+int svgd_phi_ld(svgd_handle_t c, const float *X, const float *G, int n, int64_t D, int64_t ld, float *PHI,
+                void *stream)
 {
     int rc = check_handle(c);
     if (rc) return rc;
     if (!X || !G || !PHI) return SVGD_ERR_INVALID_ARG;
-    rc = check_shape(c, n, D);
+    rc = check_shape(c, n, D, ld);
     if (rc) return rc;
-    if (overlaps(X, PHI, n, D) || overlaps(G, PHI, n, D)) return SVGD_ERR_INVALID_ARG;
+    if (overlaps(X, PHI, n, D, ld) || overlaps(G, PHI, n, D, ld)) return SVGD_ERR_INVALID_ARG;
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
-    if (is_tiny(n, D)) return run_tiny<kTinyPhi>(c, const_cast<float *>(X), G, PHI, n, D, 0.f, s);
+    if (is_tiny(n, D)) return run_tiny<kTinyPhi>(c, const_cast<float *>(X), G, PHI, n, D, ld, 0.f, s);
     c->carry_valid = false; // the partials buffer is about to be overwritten
-    rc = run_kernel_matrix(c, X, n, D, s, false);
+    rc = run_kernel_matrix(c, X, n, D, ld, s, false);
     if (rc) return rc;
-    return run_update<true, false>(c, const_cast<float *>(X), G, PHI, n, D, 0.f, s);
+    return run_update<true, false>(c, const_cast<float *>(X), G, PHI, n, D, ld, 0.f, s);
+}
+
+int svgd_phi(svgd_handle_t c, const float *X, const float *G, int n, int64_t D, float *PHI, void *stream)
+{
+    return svgd_phi_ld(c, X, G, n, D, D, PHI, stream);
 }
 
 int svgd_get_last(svgd_handle_t c, double *h_out, float *K_host, void *stream)
@@ -475,7 +498,7 @@ int swag_update_moments(float *mean, float *sqmean, const float *X, int n, int64
                         void *stream)
 {
     if (!mean || !sqmean || !X || n < 1 || D < 1 || count < 0) return SVGD_ERR_INVALID_ARG;
-    if (overlaps(mean, X, n, D) || overlaps(sqmean, X, n, D) || overlaps(mean, sqmean, n, D))
+    if (overlaps(mean, X, n, D, D) || overlaps(sqmean, X, n, D, D) || overlaps(mean, sqmean, n, D, D))
         return SVGD_ERR_INVALID_ARG;
     const int64_t total = (int64_t)n * D;
     const int64_t ngroups = (total + 3) / 4;

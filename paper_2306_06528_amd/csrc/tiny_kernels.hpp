@@ -23,7 +23,7 @@ enum TinyWhat : int {
 template <int N, int WHAT>
 __global__ __launch_bounds__(kTinyThreads) void step_tiny_kernel(float *__restrict__ X,
                                                                const float *__restrict__ G,
-                                                               float *__restrict__ PHI, int64_t D,
+                                                               float *__restrict__ PHI, int64_t D, int64_t ld,
                                                                float eps, double h_fixed,
                                                                DevState *__restrict__ st,
                                                                float *__restrict__ coef)
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(kTinyThreads) void step_tiny_kernel(float *__restri
         const bool full = (col + 4 <= D);
         f32x4 x[N];
 #pragma unroll
-        for (int j = 0; j < N; ++j) x[j] = load4(X + (int64_t)j * D, col, D, full);
+        for (int j = 0; j < N; ++j) x[j] = load4(X + (int64_t)j * ld, col, D, full);
         pair_accumulate<N>(x, acc);
     }
     double *red = sh.pr; // [kTinyThreads / 64][P], free until the bandwidth computation's first barrier
@@ -76,8 +76,8 @@ __global__ __launch_bounds__(kTinyThreads) void step_tiny_kernel(float *__restri
         f32x4 x[N], z[N];
 #pragma unroll
         for (int j = 0; j < N; ++j) {
-            x[j] = load4(X + (int64_t)j * D, col, D, full);
-            z[j] = load4(G + (int64_t)j * D, col, D, full);
+            x[j] = load4(X + (int64_t)j * ld, col, D, full);
+            z[j] = load4(G + (int64_t)j * ld, col, D, full);
         }
 #pragma unroll
         for (int j = 0; j < N; ++j) z[j] -= c2h * x[j];
@@ -87,9 +87,9 @@ __global__ __launch_bounds__(kTinyThreads) void step_tiny_kernel(float *__restri
 #pragma unroll
             for (int j = 0; j < N; ++j) a += cl[i * N + j] * z[j];
             if constexpr (WHAT == kTinyPhi)
-                store4(PHI + (int64_t)i * D, col, D, full, a);
+                store4(PHI + (int64_t)i * ld, col, D, full, a);
             else
-                store4(X + (int64_t)i * D, col, D, full, x[i] + eps * a);
+                store4(X + (int64_t)i * ld, col, D, full, x[i] + eps * a);
         }
     }
 }

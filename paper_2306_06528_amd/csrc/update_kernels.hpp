@@ -27,7 +27,7 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
                                                           float *__restrict__ PHI,
                                                           const float *__restrict__ coef,
                                                           const DevState *__restrict__ st,
-                                                          int64_t D, float eps,
+                                                          int64_t D, int64_t ld, float eps,
                                                           float *__restrict__ gram_out)
 {
     static_assert(!(CARRY && EMIT), "the pair sums are carried only when X is updated");
@@ -56,8 +56,8 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
         f32x4 x[N], z[N];
 #pragma unroll
         for (int j = 0; j < N; ++j) {
-            x[j] = load4(X + (int64_t)j * D, col, D, full);
-            z[j] = load4_stream(G + (int64_t)j * D, col, D, full);
+            x[j] = load4(X + (int64_t)j * ld, col, D, full);
+            z[j] = load4_stream(G + (int64_t)j * ld, col, D, full);
         }
 
         f32x4 m = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -75,10 +75,10 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 #pragma unroll
             for (int j = 0; j < N; ++j) acc += C[i * N + j] * z[j];
             if constexpr (EMIT) {
-                store4(PHI + (int64_t)i * D, col, D, full, acc);
+                store4(PHI + (int64_t)i * ld, col, D, full, acc);
             } else {
                 const f32x4 xn = x[i] + eps * acc;
-                store4(X + (int64_t)i * D, col, D, full, xn);
+                store4(X + (int64_t)i * ld, col, D, full, xn);
                 if constexpr (CARRY) y[i] = xn - m; // columns beyond D: x = g = 0 -> xn = 0, m = 0
             }
         }
@@ -147,7 +147,7 @@ constexpr int kUpdCarry = 64 * 32;  // floats per wave
 template <bool EMIT, bool CARRY>
 __device__ inline void update_tail_columns(float *__restrict__ X, const float *__restrict__ G,
                                            float *__restrict__ OUT, const float *__restrict__ coef,
-                                           float c2h, int n, int64_t D, int64_t col0, float eps,
+                                           float c2h, int n, int64_t D, int64_t ld, int64_t col0, float eps,
                                            float *__restrict__ lds, float *__restrict__ gram_out)
 {
     // plain per-column evaluation for the < 64 columns after the last full tile
@@ -157,8 +157,8 @@ __device__ inline void update_tail_columns(float *__restrict__ X, const float *_
     for (int j = part; j < n; j += 4) {
         float xv = 0.f, gv = 0.f;
         if (ok) {
-            xv = X[(int64_t)j * D + col0 + col];
-            gv = G[(int64_t)j * D + col0 + col];
+            xv = X[(int64_t)j * ld + col0 + col];
+            gv = G[(int64_t)j * ld + col0 + col];
         }
         xs[j * 64 + col] = xv;
         zs[j * 64 + col] = gv - c2h * xv;
@@ -175,7 +175,7 @@ __device__ inline void update_tail_columns(float *__restrict__ X, const float *_
         const float xv = xs[i * 64 + col];
         const float phi = fmaf(coef[kOffRho + i], xv, acc);
         const float out = EMIT ? phi : fmaf(eps, phi, xv);
-        if (ok) OUT[(int64_t)i * D + col0 + col] = out;
+        if (ok) OUT[(int64_t)i * ld + col0 + col] = out;
         if constexpr (CARRY) yn[i * 64 + col] = ok ? out - m : 0.f;
     }
     if constexpr (CARRY) {
@@ -214,7 +214,7 @@ template <int NB, bool EMIT, bool FULLROWS, bool CARRY>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
                         const float *__restrict__ coef, const DevState *__restrict__ st, int n,
-                        int64_t D, float eps, float *__restrict__ gram_out)
+                        int64_t D, int64_t ld, float eps, float *__restrict__ gram_out)
 {
     static_assert(!(CARRY && EMIT), "the Gram is carried only when X is updated");
     constexpr int NS = 4 * NB; // contraction steps = rows per lane
@@ -237,7 +237,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 for (int p = threadIdx.x; p < P; p += 256) tail_out[p] = 0.f;
         }
         if ((nfull << 6) < D)
-            update_tail_columns<EMIT, CARRY>(X, G, OUT, coef, c2h, n, D, nfull << 6, eps, lds, tail_out);
+            update_tail_columns<EMIT, CARRY>(X, G, OUT, coef, c2h, n, D, ld, nfull << 6, eps, lds, tail_out);
         return;
     }
 
@@ -281,11 +281,11 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     const int64_t c_begin = t0 << 6;
 
     // lane part of every load address: row 4q, column 4c; the rest is wave-uniform
-    const int64_t in_lane = (int64_t)(4 * q) * D + 4 * c16;
+    const int64_t in_lane = (int64_t)(4 * q) * ld + 4 * c16;
     // stores: lane (rl = q, p = c16) writes row urow + q; a row's misalignment in floats is
     // (a0 + row * dm) mod 32 because every tile starts at a multiple of 32 columns
-    const int64_t out_lane = (int64_t)q * D + 4 * c16;
-    const uint32_t dm = (uint32_t)D & 31u;
+    const int64_t out_lane = (int64_t)q * ld + 4 * c16;
+    const uint32_t dm = (uint32_t)ld & 31u;
     const uint32_t a0 = (uint32_t)(reinterpret_cast<uintptr_t>(OUT) >> 2) & 31u;
 
     // Software pipeline across tiles: the loads of tile t+1 are issued while tile t is being
@@ -301,11 +301,11 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     f32x4 x[NS], z[NS], xn[DBUF ? NS : 1], gn[DBUF ? NS : 1];
     auto load_x = [&](const float *xt, int s) __attribute__((always_inline)) {
         const int urow = 16 * (s >> 2) + (s & 3); // uniform part of the row index
-        if (FULLROWS || urow + 4 * q < n) x[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * D);
+        if (FULLROWS || urow + 4 * q < n) x[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * ld);
     };
     auto load_g = [&](const float *gt, int s) __attribute__((always_inline)) {
         const int urow = 16 * (s >> 2) + (s & 3);
-        if (FULLROWS || urow + 4 * q < n) z[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * D);
+        if (FULLROWS || urow + 4 * q < n) z[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * ld);
     };
     auto load_next = [&](const float *xt, const float *gt) __attribute__((always_inline)) {
         if constexpr (DBUF) {
@@ -313,8 +313,8 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             for (int s = 0; s < NS; ++s) {
                 const int urow = 16 * (s >> 2) + (s & 3);
                 if (FULLROWS || urow + 4 * q < n) {
-                    xn[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * D);
-                    gn[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * D);
+                    xn[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * ld);
+                    gn[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * ld);
                 }
             }
         }
@@ -393,7 +393,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : cur_index(rloc, o)];
             }
             if (FULLROWS || row < n) {
-                float *dst = ot + (int64_t)urow * D - ri;
+                float *dst = ot + (int64_t)urow * ld - ri;
                 if constexpr (!FIRST) {
                     __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(dst));
                 } else { // left end of the range: nothing left of c_begin is ours
@@ -499,7 +499,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             const int row = idx >> 5, cc = idx & 31;
             const int ri = (int)((a0 + (uint32_t)row * dm) & 31u);
             if (row < n && cc >= 32 - ri && c_end - 32 + cc >= c_begin)
-                OUT[(int64_t)row * D + c_end - 32 + cc] = carry[row * 32 + cc];
+                OUT[(int64_t)row * ld + c_end - 32 + cc] = carry[row * 32 + cc];
         }
     }
 

@@ -28,6 +28,12 @@ _lib.svgd_step.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, c
                            ctypes.c_float, ctypes.c_void_p]
 _lib.svgd_phi.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
                           ctypes.c_void_p, ctypes.c_void_p]
+_lib.svgd_bandwidth_ld.argtypes = [_H, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                   ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
+_lib.svgd_step_ld.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+                              ctypes.c_int64, ctypes.c_float, ctypes.c_void_p]
+_lib.svgd_phi_ld.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
+                             ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
 _lib.svgd_get_last.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p, ctypes.c_void_p]
 _lib.svgd_destroy.argtypes = [_H]
 _lib.svgd_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
@@ -41,6 +47,7 @@ _lib.svgd_last_device_error.argtypes = [_H]
 _lib.svgd_status_string.argtypes = [ctypes.c_int]
 _lib.svgd_status_string.restype = ctypes.c_char_p
 for _f in ("svgd_create", "svgd_set_bandwidth", "svgd_bandwidth", "svgd_step", "svgd_phi",
+           "svgd_bandwidth_ld", "svgd_step_ld", "svgd_phi_ld",
            "svgd_get_last", "svgd_destroy", "svgd_last_device_error", "svgd_profile_begin",
            "svgd_profile_end"):
     getattr(_lib, _f).restype = ctypes.c_int
@@ -74,6 +81,16 @@ def _dev_matrix(t: torch.Tensor, name: str):
             and t.is_contiguous()):
         raise TypeError(f"{name} must be a contiguous 2-D float32 CUDA tensor")
     return t
+
+
+def padded_rows(n: int, D: int, device="cuda", fill=None):
+    """An (n, D) view of a new (n, ld) buffer, ld = D rounded up to 32 floats: every row starts on
+    a 128-byte boundary, the layout the update kernels like best.  Returns the view."""
+    ld = (D + 31) // 32 * 32
+    buf = torch.empty(n, ld, device=device, dtype=torch.float32)
+    if fill is not None:
+        buf.fill_(fill)
+    return buf[:, :D]
 
 
 def diag_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):
@@ -110,12 +127,22 @@ class Svgd:
             raise SvgdError(rc)
         self._device = int(device) if device >= 0 else torch.cuda.current_device()
 
-    def _mat(self, t, name):
-        """A matrix argument: also on the handle's device (a pointer of another GPU would fault)."""
-        t = _dev_matrix(t, name)
+    def _rows(self, t, name):
+        """Checks a matrix argument (2-D float32, rows contiguous, on the handle's device - a
+        pointer of another GPU would fault) and returns (n, D, ld).  Kept short: at small sizes
+        a step costs less than these checks."""
+        if not isinstance(t, torch.Tensor) or t.dtype is not torch.float32 or not t.is_cuda or t.dim() != 2:
+            raise TypeError(f"{name} must be a 2-D float32 CUDA tensor")
+        (n, D), st = t.shape, t.stride()
+        if (D != 1 and st[1] != 1) or (n != 1 and st[0] < D):
+            raise TypeError(f"{name} must have contiguous rows, at least D elements apart")
         if t.get_device() != self._device:
             raise ValueError(f"{name} is on cuda:{t.get_device()}, the handle on cuda:{self._device}")
-        return t
+        return n, D, (st[0] if n != 1 else D)
+
+    def _same(self, a, b, name):
+        if a != b:
+            raise ValueError(f"{name} has (n, D, row stride) = {b}, X has {a}")
 
     def _check(self, rc):
         if rc != SVGD_OK:
@@ -128,30 +155,30 @@ class Svgd:
         self._check(_lib.svgd_forget_carry(self._h))
 
     def bandwidth(self, X, want_h=True, stream=None):
-        X = self._mat(X, "X")
-        n, D = X.shape
+        n, D, ld = self._rows(X, "X")
         out = ctypes.c_double(0.0)
-        self._check(_lib.svgd_bandwidth(self._h, X.data_ptr(), n, D,
-                                        ctypes.byref(out) if want_h else None, _stream_ptr(stream)))
+        self._check(_lib.svgd_bandwidth_ld(self._h, X.data_ptr(), n, D, ld,
+                                           ctypes.byref(out) if want_h else None, _stream_ptr(stream)))
         self._last_n = n
         return out.value if want_h else None
 
     def step(self, X, G, eps: float, stream=None):
-        X, G = self._mat(X, "X"), self._mat(G, "G")
-        if X.shape != G.shape:
-            raise ValueError("X and G must have the same shape")
-        n, D = X.shape
-        self._check(_lib.svgd_step(self._h, X.data_ptr(), G.data_ptr(), n, D, float(eps),
-                                   _stream_ptr(stream)))
+        """X <- X + eps * phi(X, G) in place.  X and G: (n, D) with contiguous rows and the same
+        row stride (dense, or views like buf[:, :D] of an (n, ld) buffer, see padded_rows)."""
+        shape = self._rows(X, "X")
+        self._same(shape, self._rows(G, "G"), "G")
+        n, D, ld = shape
+        self._check(_lib.svgd_step_ld(self._h, X.data_ptr(), G.data_ptr(), n, D, ld, float(eps),
+                                      _stream_ptr(stream)))
         self._last_n = n
 
     def phi(self, X, G, PHI, stream=None):
-        X, G, PHI = self._mat(X, "X"), self._mat(G, "G"), self._mat(PHI, "PHI")
-        if X.shape != G.shape or X.shape != PHI.shape:
-            raise ValueError("X, G and PHI must have the same shape")
-        n, D = X.shape
-        self._check(_lib.svgd_phi(self._h, X.data_ptr(), G.data_ptr(), n, D, PHI.data_ptr(),
-                                  _stream_ptr(stream)))
+        shape = self._rows(X, "X")
+        self._same(shape, self._rows(G, "G"), "G")
+        self._same(shape, self._rows(PHI, "PHI"), "PHI")
+        n, D, ld = shape
+        self._check(_lib.svgd_phi_ld(self._h, X.data_ptr(), G.data_ptr(), n, D, ld, PHI.data_ptr(),
+                                     _stream_ptr(stream)))
         self._last_n = n
 
     def get_last(self, n: int, stream=None):

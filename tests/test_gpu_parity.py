@@ -325,6 +325,65 @@ def test_config5_large_ensemble_full_size(svgd):
     _full_size_check(svgd, 5)
 
 
+def _padded(t, ld, sentinel):
+    """An (n, D) view with row stride ld of a buffer whose padding holds a sentinel."""
+    n, D = t.shape
+    buf = torch.full((n, ld), sentinel, device=t.device, dtype=t.dtype)
+    buf[:, :D] = t
+    return buf, buf[:, :D]
+
+
+@pytest.mark.parametrize("carry", [False, True])
+@pytest.mark.parametrize("n,D,ld", [(4, 1000, 1024), (4, 1000, 1003), (8, 70_001, 70_016), (8, 70_001, 70_002),
+                                    (12, 5000, 5024), (16, 8577, 8608), (20, 4099, 4100), (32, 20_001, 20_032),
+                                    (33, 1531, 1600), (64, 70_001, 70_016), (64, 70_001, 70_003), (64, 63, 64),
+                                    (1, 100, 128)])
+def test_rows_with_a_leading_dimension(svgd, n, D, ld, carry):
+    """Particles stored ld >= D floats apart (svgd_*_ld): same results as the dense layout, and
+    the floats between the rows are neither read (they hold NaN) nor written."""
+    X0, G0 = _random_problem(n, D, 3 * n + D + ld, x_std=0.3)
+    eps = 0.05
+    Xb, X = _padded(X0, ld, float("nan"))
+    Gb, G = _padded(G0, ld, float("nan"))
+    Pb, PHI = _padded(torch.zeros_like(X0), ld, 7.0)
+    ref = orc.step(X0.cpu().numpy(), G0.cpu().numpy(), eps)
+    with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM if carry else 0) as eng:
+        h_bw = eng.bandwidth(X)
+        eng.phi(X, G, PHI)
+        h, K = eng.get_last(n)
+        assert h_bw == h
+        assert abs(h - ref["h"]) / ref["h"] <= TOL_H
+        assert np.abs(K - ref["K"]).max() <= TOL_K
+        e = np.abs(PHI.cpu().numpy() - ref["phi"]).max() / np.abs(ref["phi"]).max()
+        assert e <= TOL_PHI, f"phi {e:.3e}"
+        for step in range(3):            # steps 1 and 2 use the carried sums when carry is set
+            Xh = X.cpu().numpy()
+            eng.step(X, G, eps)
+            h, K = eng.get_last(n)
+            r = orc.step(Xh, G0.cpu().numpy(), eps)
+            assert abs(h - r["h"]) / r["h"] <= TOL_H, f"step {step}"
+            assert np.abs(K - r["K"]).max() <= TOL_K, f"step {step}"
+            err = np.abs(X.cpu().numpy() - r["X_new"]).max() / np.abs(r["X_new"]).max()
+            assert err <= 1e-6, f"step {step}: {err:.3e}"
+    if ld > D:
+        assert torch.isnan(Xb[:, D:]).all() and torch.isnan(Gb[:, D:]).all(), "padding of X or G was written"
+        assert torch.all(Pb[:, D:] == 7.0), "padding of PHI was written"
+
+
+def test_mixed_leading_dimensions_are_rejected(svgd):
+    X = torch.zeros(4, 128, device="cuda")[:, :100]
+    G = torch.zeros(4, 100, device="cuda")
+    with svgd.Svgd(4, 100) as eng:
+        with pytest.raises(ValueError):
+            eng.step(X, G, 0.1)
+        with pytest.raises(TypeError):
+            eng.step(torch.zeros(100, 4, device="cuda").t(), G, 0.1)      # rows not contiguous
+    lib = svgd._lib
+    eng = svgd.Svgd(4, 100)
+    assert lib.svgd_step_ld(eng._h, X.data_ptr(), G.data_ptr(), 4, 100, 99, 0.1, None) == -1   # ld < D
+    eng.close()
+
+
 @pytest.mark.parametrize("n,D,carry", [(3, 800_000_001, True), (16, 150_000_001, False), (64, 34_000_001, True)])
 def test_more_than_2_to_31_elements(svgd, n, D, carry):
     """n * D = 2.4e9 elements (9.6 GB per array): element offsets beyond 32 bits on the vector-ALU
