@@ -25,15 +25,21 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
     # (config, carried Gram?, rows padded to 32 floats?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True, False): (4081267.5, 2797114.4),
-    (5, False, False): (4069645.0, 2795026.3),
-    (3, True, True): (250219.2, 250530.3),      # D = 2,000,000 is a multiple of 32: ld = D
-    (3, False, True): (250146.7, 250000.3),
-    (4, True, False): (369110.9, 357076.1),
-    (4, False, False): (365622.7, 355099.5),
+    (5, True, True): (2799475.0, 2795580.4),
+    (5, False, True): (2797539.9, 2793492.7),
+    (5, True, False): (4080535.1, 2797113.9),
+    (5, False, False): (4069378.5, 2795026.6),
+    (3, True, True): (250259.0, 250530.4),      # D = 2,000,000 is a multiple of 32: ld = D either way
+    (3, False, True): (250168.8, 250001.2),
+    (3, True, False): (250258.7, 250530.3),
+    (3, False, False): (250169.9, 250000.4),
+    (4, True, True): (349289.7, 349266.5),
+    (4, False, True): (349250.1, 349186.5),
+    (4, True, False): (368905.3, 357034.5),
+    (4, False, False): (365538.4, 355119.9),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "5a189b371f429f73ac09e263f83ef7c0dfc632e8f84ee30f04dfd9e834453f58"
+TRAFFIC_SOURCE_SHA256 = "f73b18234101a0a12f3cad0ea5d6a9a1e33effe5d4b36c3b8e284b2ffb912576"
 
 
 def kernel_source_hash():
@@ -122,7 +128,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=20,
+                    help="untimed steps first (the chip needs some 30 ms of work to reach its steady clocks)")
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default 5: n=64, D=11,173,962)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-gram", action="store_true",
