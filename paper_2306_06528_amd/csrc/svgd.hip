@@ -241,7 +241,15 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int grid = clampi((nfull + 3) / 4, 1, max_workers) + 1;
         const int NB = (n + 15) / 16;
         if (CARRY) c->carry_nparts = grid; // one partial per workgroup, the tail's included
-#define UPD(NBV, FULL) update_mfma_kernel<NBV, EMIT, FULL, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials)
+        // rows that all start on a 128-byte boundary need no re-aligned stores
+        const bool aligned = !EMIT && (ld & 31) == 0 && (reinterpret_cast<uintptr_t>(X) & 127) == 0;
+#define UPD(NBV, FULL)                                                                                       \
+    do {                                                                                                     \
+        if (!EMIT && aligned)                                                                                \
+            update_mfma_kernel<NBV, false, FULL, CARRY, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials); \
+        else                                                                                                 \
+            update_mfma_kernel<NBV, EMIT, FULL, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials);       \
+    } while (0)
         if (n == 16) UPD(1, true);
         else if (NB == 1) UPD(1, false);
         else if (n == 32) UPD(2, true);

@@ -135,7 +135,10 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 //     r_i = (address of row i at the tile's first column, in floats) mod 32: that window starts
 //     on a 128-byte boundary, and its first r_i columns are the previous tile's last ones, kept
 //     in LDS (carry, 64 x 32 floats per wave).
-// Every store instruction then writes whole cache lines.  Only the two ends of a wave's range
+// Every store instruction then writes whole cache lines.  (ALIGNED: the caller guarantees that
+// every row starts on a 128-byte boundary - ld a multiple of 32 floats, base pointer aligned; then
+// r_i = 0 for all rows, the windows are the tiles, and the results are stored straight from the
+// registers that computed them, with no staging at all unless the Gram operands need it.)  Only the two ends of a wave's range
 // see partial lines: the first tile masks what lies left of the range, and the carry is flushed
 // element-wise after the last tile.  Columns beyond the last full tile (D mod 64) are done by
 // one extra workgroup with a plain loop.  Rows >= n (n not a multiple of 16) are neither loaded
@@ -210,7 +213,7 @@ __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 // The pieces of one group are written interleaved and sit in one basic block (no branches in the
 // steady-state tile), which lets the scheduler fill the MFMA shadows.  The first tile of a range,
 // which has to mask its left edge, is a separate, branchy instance of the same code.
-template <int NB, bool EMIT, bool FULLROWS, bool CARRY>
+template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
                         const float *__restrict__ coef, const DevState *__restrict__ st, int n,
@@ -444,13 +447,13 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                     // the four store groups of the previous block are spread over the NB step groups
 #pragma unroll
                     for (int k = 0; k < 4; ++k)
-                        if (k * NB / 4 == sg) emit_group(bi - 1, k);
+                        if (!ALIGNED && k * NB / 4 == sg) emit_group(bi - 1, k);
                     if constexpr (CARRY) {
                         if (sg < bi) gram_pair(sg, bi - 1); // pairs (0..bi-1, bi-1): one per step group
                     }
                 }
             }
-            if (bi > 0) carry_copy(bi - 1);
+            if (!ALIGNED && bi > 0) carry_copy(bi - 1);
             // epilogue for rows 16bi + 4q + r, then stage the block in LDS
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
@@ -461,7 +464,12 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                     const float phi = fmaf(rho[s], x[s][t], acc[t][r]);
                     o[t] = EMIT ? phi : fmaf(eps, phi, x[s][t]);
                 }
-                *reinterpret_cast<f32x4 *>(&cur[cur_index(4 * q + r, 4 * c16)]) = o;
+                if constexpr (ALIGNED) { // the lane's 16 bytes lie where it loaded x from: whole lines per quarter-wave
+                    if (FULLROWS || 16 * bi + 4 * q + r < n)
+                        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(OUT + in_lane + base + (int64_t)(16 * bi + r) * ld));
+                }
+                if constexpr (!ALIGNED || CARRY) // staged for the re-aligned stores and/or as Gram operands
+                    *reinterpret_cast<f32x4 *>(&cur[cur_index(4 * q + r, 4 * c16)]) = o;
             }
             if constexpr (!DBUF) { // x rows of this block are dead: fetch the next tile's
 #pragma unroll
@@ -477,23 +485,25 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         // E(NB-1) interleaved with G(NB-1)
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-            emit_group(NB - 1, k);
+            if constexpr (!ALIGNED) emit_group(NB - 1, k);
             if constexpr (CARRY) {
 #pragma unroll
                 for (int b0 = 0; b0 < NB; ++b0)
                     if (b0 * 4 / NB == k) gram_pair(b0, NB - 1);
             }
         }
-        carry_copy(NB - 1);
+        if constexpr (!ALIGNED) carry_copy(NB - 1);
     };
 
-    if (t0 < t1) {
+    if constexpr (ALIGNED) { // no left edge to mask
+        for (int64_t tile = t0; tile < t1; ++tile) process_tile(std::false_type{}, tile);
+    } else if (t0 < t1) {
         process_tile(std::true_type{}, t0);
         for (int64_t tile = t0 + 1; tile < t1; ++tile) process_tile(std::false_type{}, tile);
     }
 
     // flush: the last r_i columns of the range are still in the carry
-    if (t1 > t0) {
+    if (!ALIGNED && t1 > t0) {
         const int64_t c_end = t1 << 6;
         for (int idx = lane; idx < 16 * NB * 32; idx += 64) {
             const int row = idx >> 5, cc = idx & 31;
