@@ -17,7 +17,8 @@
  *
  * Conventions for every entry point
  *   - X, G, PHI are DEVICE pointers to n x D fp32, row-major, leading dimension D (row i starts
- *     at element i*D).  Only 4-byte alignment is required.  D is 64-bit.
+ *     at element i*D) or, in the *_ld calls, ld >= D.  Only 4-byte alignment is required.  D and
+ *     ld are 64-bit.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued on it; calls return before the work completes unless stated otherwise.
  *   - The caller owns X, G, PHI.  The handle owns its scratch (partial sums, K, h), allocated
