@@ -184,28 +184,32 @@ def main():
         torch.cuda.synchronize()
         del scratch
 
-    def timed(flags, Xv, Gv, profile):
-        """Warm-up, then K timed steps; optionally K more with per-kernel HIP events."""
+    def timed(flags, Xv, Gv, kinds=None):
+        """Warm-up, then K timed steps.  `kinds`: kernels of these kinds are bracketed by HIP
+        events on the launch stream during the timed steps (recorded by the library; two event
+        records per timed kernel, a few microseconds each)."""
         with svgd.Svgd(n, D, 0, flags=flags) as eng:
             for _ in range(args.warmup):
                 eng.step(Xv, Gv, eps, stream=stream)
             torch.cuda.synchronize()
+            if kinds:
+                eng.profile_begin(kinds)
             t0 = time.perf_counter()
             for _ in range(args.steps):
                 eng.step(Xv, Gv, eps, stream=stream)
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
-            prof = None
-            if profile:   # per-kernel durations over the same number of steps, events on the launch stream
-                eng.profile_begin()
-                for _ in range(args.steps):
-                    eng.step(Xv, Gv, eps, stream=stream)
-                prof = eng.profile_end()
-                torch.cuda.synchronize()
+            prof = eng.profile_end() if kinds else None
         return dt, prof
 
     carry = not args.separate_gram
-    dt, prof = timed(svgd.FLAG_CARRY_GRAM if carry else 0, X, G, True)
+    flags = svgd.FLAG_CARRY_GRAM if carry else 0
+    # the timed region: K steps, the dominant kernel (update) timed by events inside it
+    dt, prof_upd = timed(flags, X, G, kinds=("update",))
+    # the same K steps again, once with every kernel timed (the per-kernel breakdown) and once
+    # with no events at all (what the events in the timed region cost)
+    _, prof = timed(flags, X, G, kinds=svgd.KERNEL_KINDS)
+    dt_plain, _ = timed(flags, X, G)
 
     def side(dt_side, **what):
         what.update({"ms_per_step": dt_side * 1e3 / args.steps, "value": n * D * args.steps / dt_side})
@@ -215,19 +219,19 @@ def main():
     # (b) with densely packed rows (ld = D)
     alt = None
     if carry:
-        alt = side(timed(0, X, G, False)[0], gram="separate pass")
+        alt = side(timed(0, X, G)[0], gram="separate pass")
     alt_dense = None
     if padded and ld != D:
         _, Xd = laid_out(wl.X0, False)
         _, Gd = laid_out(G0, False)
-        alt_dense = side(timed(svgd.FLAG_CARRY_GRAM if carry else 0, Xd, Gd, False)[0], ld=D)
+        alt_dense = side(timed(flags, Xd, Gd)[0], ld=D)
         del Xd, Gd
 
     assert torch.isfinite(X).all().item(), "X went non-finite during the benchmark"
     ms_per_step = dt * 1e3 / args.steps
     value = n * D * args.steps / dt
     kern_ms = {k: (ms / max(c, 1)) for k, (ms, c) in prof.items()}
-    upd_ms = kern_ms["update"]
+    upd_ms = prof_upd["update"][0] / max(prof_upd["update"][1], 1)   # over the timed steps
     upd_gbs = UPDATE_BYTES_PER_PARAM * n * D / (upd_ms * 1e-3) / 1e9
     gram_gbs = 4 * n * D / (kern_ms["gram"] * 1e-3) / 1e9 if kern_ms["gram"] > 0 else None
 
@@ -257,6 +261,7 @@ def main():
         "step_hbm_frac": (UPDATE_BYTES_PER_PARAM if carry else STEP_BYTES_PER_PARAM) * n * D
                          / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": kern_ms,
+        "ms_per_step_without_events": dt_plain * 1e3 / args.steps,
         "separate_gram": alt,
         "dense_rows": alt_dense,
         "gram_gbs": gram_gbs,

@@ -146,6 +146,9 @@ enum svgd_kernel_kind {
     SVGD_KERNEL_KINDS = 4
 };
 int svgd_profile_begin(svgd_handle_t h);
+/* The same, timing only the kinds whose bit (1u << kind) is set in `kinds`: every timed kernel
+ * costs two event records on the stream, a few microseconds between kernels. */
+int svgd_profile_begin_kinds(svgd_handle_t h, unsigned kinds);
 int svgd_profile_end(svgd_handle_t h, double *ms_sum, int *count);
 
 /*

@@ -47,6 +47,7 @@ struct svgd_ctx {
     float *coef;      // kCoefFloats
     // optional per-kernel timing (svgd_profile_begin/end): event pairs recorded around launches
     bool profiling;
+    unsigned profile_kinds; // bit k set: kernels of kind k are timed
     std::vector<hipEvent_t> ev_pool; // 2 events per record
     std::vector<int> ev_kind;        // SVGD_KERNEL_* of each record
 };
@@ -98,7 +99,7 @@ struct KernelTimer {
     size_t slot = (size_t)-1;
     KernelTimer(svgd_ctx *ctx, int kind, hipStream_t stream) : c(ctx), s(stream)
     {
-        if (!c->profiling || c->ev_kind.size() >= kMaxProfileRecords) return;
+        if (!c->profiling || !((c->profile_kinds >> kind) & 1u) || c->ev_kind.size() >= kMaxProfileRecords) return;
         const size_t idx = c->ev_kind.size();
         while (c->ev_pool.size() < 2 * (idx + 1)) {
             hipEvent_t e;
@@ -333,6 +334,7 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
     c->state = nullptr;
     c->coef = nullptr;
     c->profiling = false;
+    c->profile_kinds = ~0u;
 
     hipError_t e;
     int dev = device_id;
@@ -520,14 +522,18 @@ int swag_update_moments(float *mean, float *sqmean, const float *X, int n, int64
     return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
 }
 
-int svgd_profile_begin(svgd_handle_t c)
+int svgd_profile_begin_kinds(svgd_handle_t c, unsigned kinds)
 {
     int rc = check_handle(c);
     if (rc) return rc;
+    if ((kinds & ((1u << SVGD_KERNEL_KINDS) - 1u)) == 0) return SVGD_ERR_INVALID_ARG;
     c->ev_kind.clear();
+    c->profile_kinds = kinds;
     c->profiling = true;
     return SVGD_OK;
 }
+
+int svgd_profile_begin(svgd_handle_t c) { return svgd_profile_begin_kinds(c, ~0u); }
 
 int svgd_profile_end(svgd_handle_t c, double *ms_sum, int *count)
 {

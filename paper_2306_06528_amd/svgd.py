@@ -42,6 +42,8 @@ _lib.swag_update_moments.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_
                                      ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p]
 _lib.swag_update_moments.restype = ctypes.c_int
 _lib.svgd_profile_begin.argtypes = [_H]
+_lib.svgd_profile_begin_kinds.argtypes = [_H, ctypes.c_uint]
+_lib.svgd_profile_begin_kinds.restype = ctypes.c_int
 _lib.svgd_profile_end.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
 _lib.svgd_last_device_error.argtypes = [_H]
 _lib.svgd_status_string.argtypes = [ctypes.c_int]
@@ -193,8 +195,15 @@ class Svgd:
                                        _stream_ptr(stream)))
         return h.value, K
 
-    def profile_begin(self):
-        self._check(_lib.svgd_profile_begin(self._h))
+    def profile_begin(self, kinds=None):
+        """Time every kernel launched from now on, or only the given kinds (names from KERNEL_KINDS)."""
+        if kinds is None:
+            self._check(_lib.svgd_profile_begin(self._h))
+        else:
+            mask = 0
+            for k in kinds:
+                mask |= 1 << KERNEL_KINDS.index(k)
+            self._check(_lib.svgd_profile_begin_kinds(self._h, mask))
 
     def profile_end(self):
         """{kind: (total_ms, launches)} for the kernels launched since profile_begin()."""
