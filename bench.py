@@ -25,18 +25,18 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
     # (config, carried Gram?, rows padded to 32 floats?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True, True): (2796046.6, 2795580.1),
-    (5, False, True): (2796801.5, 2793492.0),
-    (5, True, False): (4080578.8, 2797114.5),
-    (5, False, False): (4070124.8, 2795026.3),
-    (3, True, True): (250153.2, 250530.5),      # D = 2,000,000 is a multiple of 32: ld = D either way
-    (3, False, True): (250108.5, 250000.0),
-    (3, True, False): (250155.2, 250530.5),
-    (3, False, False): (250106.5, 250000.0),
-    (4, True, True): (349292.2, 349266.5),
-    (4, False, True): (349251.9, 349186.5),
-    (4, True, False): (368818.1, 356955.3),
-    (4, False, False): (365471.3, 355062.2),
+    (5, True, True): (2796226.0, 2795580.1),
+    (5, False, True): (2796826.3, 2793492.0),
+    (5, True, False): (4080402.5, 2797114.4),
+    (5, False, False): (4069870.7, 2795026.4),
+    (3, True, True): (250153.5, 250530.6),      # D = 2,000,000 is a multiple of 32: ld = D either way
+    (3, False, True): (250111.0, 250000.0),
+    (3, True, False): (250153.2, 250530.8),
+    (3, False, False): (250104.5, 250000.0),
+    (4, True, True): (349292.0, 349266.5),
+    (4, False, True): (349251.7, 349186.5),
+    (4, True, False): (368839.8, 356954.8),
+    (4, False, False): (365488.0, 355074.7),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
 TRAFFIC_SOURCE_SHA256 = "1e2409314e7619f8bbdf6f212747d49523de0e1df721afb21758b8893d365cce"
