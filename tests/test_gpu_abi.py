@@ -67,3 +67,22 @@ def test_binding_raises(mod):
     eng.close()
     with pytest.raises(mod.SvgdError):
         mod.Svgd(65, 100)
+
+
+def test_profiling_selects_kernel_kinds(mod):
+    X = torch.randn(32, 50_000, device="cuda")
+    G = torch.randn_like(X)
+    with mod.Svgd(32, 50_000) as eng:
+        eng.profile_begin()
+        eng.step(X, G, 0.01)
+        prof = eng.profile_end()
+        assert [prof[k][1] for k in mod.KERNEL_KINDS] == [1, 1, 1, 1]
+        assert all(prof[k][0] > 0 for k in mod.KERNEL_KINDS)
+        eng.profile_begin(("update",))
+        eng.step(X, G, 0.01)
+        eng.step(X, G, 0.01)
+        prof = eng.profile_end()
+        assert [prof[k][1] for k in mod.KERNEL_KINDS] == [0, 0, 0, 2]
+        assert mod._lib.svgd_profile_begin_kinds(eng._h, 0) == -1       # no kind selected
+        eng.step(X, G, 0.01)                                            # recording is off again
+        assert [v[1] for v in eng.profile_end().values()] == [0, 0, 0, 0]
