@@ -182,6 +182,28 @@ def test_fixed_bandwidth(svgd, n):
     check_one_step(svgd, X, G, 1e-3, h_fixed=2 * ell * ell)
 
 
+@pytest.mark.parametrize("n,D", [(4, 1000), (8, 50_003), (16, 8577), (64, 20_001)])
+def test_fixed_bandwidth_limits(svgd, n, D):
+    """h very large: K = 1 and phi_i = mean_j g_j;  h very small: K = I and phi_i = g_i / n (the
+    repulsive coefficient (2/h)/n then multiplies x_i - x_i, which the kernels evaluate as a
+    difference of two equal products)."""
+    X, G = _random_problem(n, D, 41 * n + D)
+    PHI = torch.empty_like(X)
+    with svgd.Svgd(n, D) as eng:
+        eng.set_bandwidth(1e30)
+        eng.phi(X, G, PHI)
+        h, K = eng.get_last(n)
+        assert h == 1e30 and np.all(K == 1.0)
+        want = G.double().mean(0, keepdim=True).expand(n, D)
+        assert (PHI.double() - want).abs().max().item() / want.abs().max().item() <= TOL_PHI
+        eng.set_bandwidth(0.05)          # d2 is about 2 D: exp(-d2 / h) underflows to 0
+        eng.phi(X, G, PHI)
+        h, K = eng.get_last(n)
+        assert h == 0.05 and np.array_equal(K, np.eye(n, dtype=np.float32))
+        want = G.double() / n
+        assert (PHI.double() - want).abs().max().item() / want.abs().max().item() <= TOL_PHI
+
+
 def test_handle_reuse_across_shapes(svgd):
     """One handle, several (n, D) in a row: no state leaks from one call to the next."""
     with svgd.Svgd(64, 50_000) as eng:

@@ -369,3 +369,34 @@ def test_pins_catch_planted_mistake(mut):
         except (AssertionError, FloatingPointError, ValueError, ZeroDivisionError):
             caught.append(pin.__name__)
     assert caught, f"no pin notices the planted mistake {mut!r}"
+
+
+# ----------------------------------------------------------------------------------------------
+# the fixed-bandwidth mode (the paper's own kernel, App. B.2: k = exp(-|.|^2 / (2 l^2)), h = 2 l^2)
+# ----------------------------------------------------------------------------------------------
+def test_fixed_bandwidth_matches_library_kernel():
+    r = _rng(21)
+    X, G = r.normal(size=(7, 11)), r.normal(size=(7, 11))
+    ell = 1.7
+    s = orc.step(X, G, 0.1, h_fixed=2 * ell * ell)
+    assert s["h"] == 2 * ell * ell
+    np.testing.assert_allclose(s["K"], rbf_kernel(X, gamma=1.0 / (2 * ell * ell)), rtol=1e-13)
+    # phi from the definition, pair by pair
+    n = 7
+    want = np.zeros_like(X)
+    for i in range(n):
+        for j in range(n):
+            want[i] += s["K"][i, j] * G[j] + (2.0 / s["h"]) * s["K"][i, j] * (X[i] - X[j])
+    np.testing.assert_allclose(s["phi"], want / n, rtol=1e-12)
+
+
+def test_fixed_bandwidth_limits():
+    """h -> infinity: K -> 1 and phi_i -> mean_j g_j;  h -> 0: K -> I and phi_i -> g_i / n."""
+    r = _rng(22)
+    X, G = r.normal(size=(5, 8)), r.normal(size=(5, 8))
+    s = orc.step(X, G, 0.1, h_fixed=1e30)
+    np.testing.assert_allclose(s["K"], 1.0, rtol=0, atol=1e-15)
+    np.testing.assert_allclose(s["phi"], np.repeat(G.mean(0, keepdims=True), 5, 0), rtol=1e-12)
+    s = orc.step(X, G, 0.1, h_fixed=1e-30)
+    np.testing.assert_array_equal(s["K"], np.eye(5))
+    np.testing.assert_allclose(s["phi"], G / 5, rtol=1e-15)
