@@ -39,7 +39,7 @@ TRAFFIC_COUNTERS = {
     (4, False, False): (365488.0, 355074.7),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "1e2409314e7619f8bbdf6f212747d49523de0e1df721afb21758b8893d365cce"
+TRAFFIC_SOURCE_SHA256 = "5c00d2dd00cbed9b280e10922638e51cf86004f55891e81d90b1c81fb6c2a2ec"
 
 
 def kernel_source_hash():

@@ -126,7 +126,7 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 // epilogue and nothing crosses lanes.  The A operands (C re-ordered by the bandwidth kernel) sit
 // in LDS, shared by the workgroup's 4 waves, and are re-read per output block.
 //
-// Stores.  A row starts at i*D floats, so for general D the rows are not 128-byte aligned and a
+// Stores.  A row starts at i*ld floats, so in general the rows are not 128-byte aligned and a
 // store of "the tile's columns" would cut cache lines in two for almost every row; partial-line
 // writes cost far more HBM time than they carry bytes.  Loads do not care.  So each wave
 //   - owns a CONTIGUOUS range of tiles and walks it left to right,
@@ -135,14 +135,17 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 //     r_i = (address of row i at the tile's first column, in floats) mod 32: that window starts
 //     on a 128-byte boundary, and its first r_i columns are the previous tile's last ones, kept
 //     in LDS (carry, 64 x 32 floats per wave).
-// Every store instruction then writes whole cache lines.  (ALIGNED: the caller guarantees that
-// every row starts on a 128-byte boundary - ld a multiple of 32 floats, base pointer aligned; then
-// r_i = 0 for all rows, the windows are the tiles, and the results are stored straight from the
-// registers that computed them, with no staging at all unless the Gram operands need it.)  Only the two ends of a wave's range
+// Every store instruction then writes whole cache lines.  Only the two ends of a wave's range
 // see partial lines: the first tile masks what lies left of the range, and the carry is flushed
-// element-wise after the last tile.  Columns beyond the last full tile (D mod 64) are done by
-// one extra workgroup with a plain loop.  Rows >= n (n not a multiple of 16) are neither loaded
-// nor stored; their A entries are zero.
+// element-wise after the last tile.
+// ALIGNED: the caller guarantees that every row starts on a 128-byte boundary (ld a multiple of
+// 32 floats, base pointer aligned).  Then r_i = 0 for all rows, the windows are the tiles, and
+// the results are stored straight from the registers that computed them - no staging at all
+// unless the Gram operands need it.
+// Columns beyond the last full tile (D mod 64) are done by one extra workgroup with a plain
+// loop.  Rows >= n (n not a multiple of 16) are neither loaded nor stored; their A entries are
+// zero (their contraction steps still run: skipping them behind wave-uniform branches cost more
+// than it saved, see below).
 // ---------------------------------------------------------------------------------------------
 constexpr int kUpdCur = 16 * 64;    // floats per wave
 constexpr int kUpdCarry = 64 * 32;  // floats per wave
@@ -211,8 +214,9 @@ __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 // with M(b) = the MFMAs and epilogue of output block b, E(b) = the aligned stores of block b
 // (LDS reads, address arithmetic, global stores) and G(b) = the Gram MFMAs of block b (CARRY).
 // The pieces of one group are written interleaved and sit in one basic block (no branches in the
-// steady-state tile), which lets the scheduler fill the MFMA shadows.  The first tile of a range,
-// which has to mask its left edge, is a separate, branchy instance of the same code.
+// steady-state tile), which lets the scheduler fill the MFMA shadows; a handful of wave-uniform
+// branches inside the tile made it 20-30 % slower when tried.  The first tile of a range, which
+// has to mask its left edge, is a separate, branchy instance of the same code.
 template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
