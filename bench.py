@@ -54,6 +54,17 @@ UPDATE_BYTES_PER_PARAM = 12    # read X, read G, write X
 STEP_BYTES_PER_PARAM = 16      # + the Gram pass reads X once more
 
 
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def cpu_baseline(wl):
     """Times the fp64 CPU oracle as it stands on a bounded column sample of the same workload."""
     import numpy as np
@@ -70,6 +81,7 @@ def cpu_baseline(wl):
         "value": n * ds / dt,
         "unit": "particle-params/s",
         "cores": svgd_oracle.num_threads(),
+        "cpu": cpu_model(),
         "kind": "oracle",
         "sample": f"one fp64 oracle step on the first {ds} of {wl.D} columns, all {n} particles "
                   f"({dt:.1f} s)",
@@ -184,47 +196,96 @@ def main():
         torch.cuda.synchronize()
         del scratch
 
-    def timed(flags, Xv, Gv, kinds=None):
+    def timed(flags, Xv, Gv, kinds=None, per_step=False):
         """Warm-up, then K timed steps.  `kinds`: kernels of these kinds are bracketed by HIP
-        events on the launch stream during the timed steps (recorded by the library; two event
-        records per timed kernel, a few microseconds each)."""
+        events on the launch stream during the timed steps (recorded by the library from a pool
+        created beforehand; two event records per timed kernel, a few microseconds each).
+        per_step: one event per step boundary on the launch stream instead (step-to-step times).
+        Returns (wall seconds, {kind: (ms, launches)} or None, per-launch or per-step ms list)."""
         with svgd.Svgd(n, D, 0, flags=flags) as eng:
             for _ in range(args.warmup):
                 eng.step(Xv, Gv, eps, stream=stream)
-            torch.cuda.synchronize()
+            marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)] if per_step else None
             if kinds:
                 eng.profile_begin(kinds)
+            torch.cuda.synchronize()
             t0 = time.perf_counter()
-            for _ in range(args.steps):
+            for k in range(args.steps):
+                if per_step:
+                    marks[k].record(stream)
                 eng.step(Xv, Gv, eps, stream=stream)
+            if per_step:
+                marks[-1].record(stream)
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
-            prof = eng.profile_end() if kinds else None
-        return dt, prof
+            prof, recs = eng.profile_end_records() if kinds else (None, None)
+            if per_step:
+                recs = [marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps)]
+        return dt, prof, recs
+
+    def stats(ms_list):
+        v = sorted(ms_list)
+        return {"median": v[len(v) // 2] if len(v) % 2 else 0.5 * (v[len(v) // 2 - 1] + v[len(v) // 2]),
+                "min": v[0], "max": v[-1], "mean": sum(v) / len(v)}
+
+    def triad_ceiling(Xv, Gv):
+        """What the memory system gives the update's traffic and nothing else: x += s*g in place
+        over the same row streams of the same buffers (s = 0: X keeps its values), best of the two
+        access patterns and a few grid sizes.  GB/s at 12 bytes per element."""
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        best = None
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        for pattern in (0, 1):
+            for per_cu in (1, 2, 4, 8):
+                for _ in range(3):
+                    svgd.diag_axpy_rows(Xv, Gv, 0.0, pattern, cus * per_cu, stream=stream)
+                e0.record(stream)
+                for _ in range(reps):
+                    svgd.diag_axpy_rows(Xv, Gv, 0.0, pattern, cus * per_cu, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / reps
+                gbs = UPDATE_BYTES_PER_PARAM * n * D / (ms * 1e-3) / 1e9
+                if best is None or gbs > best["gbs"]:
+                    best = {"gbs": gbs, "ms": ms, "pattern": pattern, "workgroups": cus * per_cu}
+        return best
 
     carry = not args.separate_gram
     flags = svgd.FLAG_CARRY_GRAM if carry else 0
     # the timed region: K steps, the dominant kernel (update) timed by events inside it
-    dt, prof_upd = timed(flags, X, G, kinds=("update",))
-    # the same K steps again, once with every kernel timed (the per-kernel breakdown) and once
-    # with no events at all (what the events in the timed region cost)
-    _, prof = timed(flags, X, G, kinds=svgd.KERNEL_KINDS)
-    dt_plain, _ = timed(flags, X, G)
+    dt, prof_upd, recs_upd = timed(flags, X, G, kinds=("update",))
+    # the same K steps again: with every kernel timed (the per-kernel breakdown), with one event
+    # per step (median / min step time), and with no events at all (what the events cost)
+    _, prof, _ = timed(flags, X, G, kinds=svgd.KERNEL_KINDS)
+    _, _, step_ms = timed(flags, X, G, per_step=True)
+    dt_plain, _, _ = timed(flags, X, G)
+    ceiling = triad_ceiling(X, G)
 
-    def side(dt_side, **what):
-        what.update({"ms_per_step": dt_side * 1e3 / args.steps, "value": n * D * args.steps / dt_side})
+    def side(res, bytes_per_param, **what):
+        dt_side = res[0]
+        what.update({"ms_per_step": dt_side * 1e3 / args.steps, "value": n * D * args.steps / dt_side,
+                     "step_hbm_frac": bytes_per_param * n * D / (dt_side / args.steps) / 1e9 / HBM_PEAK_GBS})
         return what
 
     # for reference, the same workload (a) with the pairwise-d2 pass as its own kernel every step,
-    # (b) with densely packed rows (ld = D)
+    # (b) with densely packed rows (ld = D), (c) both: the plain svgd_step(X, G, n, D, eps, stream)
+    # of the four-call ABI on a handle without flags - 16 bytes per particle-param
     alt = None
     if carry:
-        alt = side(timed(0, X, G)[0], gram="separate pass")
-    alt_dense = None
-    if padded and ld != D:
+        alt = side(timed(0, X, G), STEP_BYTES_PER_PARAM, gram="separate pass")
+    alt_dense = alt_plain = None
+    if padded:
         _, Xd = laid_out(wl.X0, False)
         _, Gd = laid_out(G0, False)
-        alt_dense = side(timed(flags, Xd, Gd)[0], ld=D)
+        if ld != D:
+            alt_dense = side(timed(flags, Xd, Gd), UPDATE_BYTES_PER_PARAM if carry else STEP_BYTES_PER_PARAM, ld=D)
+        res = timed(0, Xd, Gd, kinds=("update",))
+        alt_plain = side(res, STEP_BYTES_PER_PARAM, ld=D, gram="separate pass",
+                         call="svgd_step(handle, X, G, n, D, eps, stream), handle flags = 0")
+        u_ms = res[1]["update"][0] / max(res[1]["update"][1], 1)
+        alt_plain["update_kernel_ms"] = u_ms
+        alt_plain["update_kernel_hbm_frac"] = UPDATE_BYTES_PER_PARAM * n * D / (u_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
         del Xd, Gd
 
     assert torch.isfinite(X).all().item(), "X went non-finite during the benchmark"
@@ -262,8 +323,11 @@ def main():
                          / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": kern_ms,
         "ms_per_step_without_events": dt_plain * 1e3 / args.steps,
+        "step_ms": stats(step_ms),
+        "update_kernel_ms": stats([ms for _, ms in recs_upd]),
         "separate_gram": alt,
         "dense_rows": alt_dense,
+        "plain_svgd_step": alt_plain,
         "gram_gbs": gram_gbs,
         "roofline": {
             "kernel": "step_tiny_kernel (the whole step in one workgroup)" if tiny else
@@ -276,6 +340,12 @@ def main():
             "unit": "GB/s",
             "frac": upd_gbs / HBM_PEAK_GBS,
             "traffic": traffic,
+            # the same bytes moved by a kernel that does nothing else (svgd_diag_axpy_rows on the
+            # same X and G, in the same run): the practical ceiling, and the update against it
+            "ceiling": ceiling["gbs"],
+            "ceiling_kernel": f"diag_axpy_rows_kernel<{ceiling['pattern']}>, {ceiling['workgroups']} workgroups, "
+                              f"{ceiling['ms']:.4f} ms",
+            "frac_of_ceiling": upd_gbs / ceiling["gbs"],
         },
     }
     if not args.no_cpu_baseline:

@@ -11,9 +11,10 @@
  *     phi_i  = (1/n) sum_j [ K_ij g_j + (2/h) K_ij (x_i - x_j) ]
  *     x_i   <- x_i + eps * phi_i                               (every phi_i from the pre-step X)
  *
- * Particle i is the flattened parameter vector of one network (App. B.2: flatten(params)); g_i is
- * its score grad log p(x_i) (a caller holding loss gradients passes g = -grad; parameters
- * without a gradient contribute zeros, as in the paper's routine).
+ * Particle i is the flattened parameter vector of one network (App. B.2: every particle's
+ * parameters are gathered into one flat vector); g_i is its score grad log p(x_i) (a caller
+ * holding loss gradients passes g = -grad; parameters without a gradient contribute zeros, as
+ * in the paper's routine).
  *
  * Conventions for every entry point
  *   - X, G, PHI are DEVICE pointers to n x D fp32, row-major, leading dimension D (row i starts
@@ -23,8 +24,9 @@
  *     enqueued on it; calls return before the work completes unless stated otherwise.
  *   - The caller owns X, G, PHI.  The handle owns its scratch (partial sums, K, h), allocated
  *     once in svgd_create and freed in svgd_destroy; svgd_step/svgd_phi/svgd_bandwidth never
- *     allocate.  One handle must not be used from two streams or two host threads at once
- *     (different handles are independent).
+ *     allocate.  The calls on one handle must be stream-ordered: one host thread at a time, and
+ *     a call on another stream than the previous one only after the caller has ordered that
+ *     stream behind the earlier work (different handles are independent).
  *   - Return value: SVGD_OK (0) or a negative svgd_status.  No entry point aborts or throws.
  *     Non-finite DATA is not checked and propagates as IEEE NaN/Inf.
  */
@@ -57,14 +59,19 @@ enum svgd_status {
  * also accumulates the pairwise sums of the NEW X, and the next svgd_step on the same (X, n, D)
  * skips its own pass over X.  The caller promises that between two svgd_step calls X is modified
  * by nobody else; after touching X (or to be safe) call svgd_forget_carry.  svgd_bandwidth and
- * svgd_phi always recompute from X and drop the carried sums.
+ * svgd_phi always recompute from X and drop the carried sums, and so does a svgd_step on another
+ * stream than the step that produced them.
  */
 #define SVGD_FLAG_CARRY_GRAM 1u
 
 /*
  * Create a handle for problems up to max_n particles (1..SVGD_MAX_PARTICLES) of up to max_D
- * parameters each on HIP device `device_id` (-1 = the current device).  `flags` is 0 or SVGD_FLAG_CARRY_GRAM.
- * Allocates the handle's device scratch (about 20 MB).  On success *out receives the handle.
+ * parameters each on HIP device `device_id` (-1 = the current device); the sizes play the part of
+ * the paper's `num_particles` and of the flattened parameter count of its networks (App. B.2, the
+ * arguments of the top-level SVGD inference call; its `lengthscale` is svgd_set_bandwidth, its
+ * `lr` the eps of svgd_step).  `flags` is 0 or SVGD_FLAG_CARRY_GRAM.  Allocates the handle's
+ * device scratch: 8192 * max_n * (max_n + 1) / 2 bytes of partial sums (17 MB at max_n = 64) and
+ * about 0.2 MB of tables.  On success *out receives the handle.
  */
 int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uint32_t flags);
 
@@ -89,14 +96,16 @@ int svgd_bandwidth(svgd_handle_t h, const float *X, int n, int64_t D, double *h_
 
 /*
  * One whole SVGD step, in place: X <- X + eps * phi(X, G).  X (device, n x D) is read, then
- * overwritten; G (device, n x D) is read only (App. B.2: kernel, kernel-gradient accumulation and
- * the followers' `p.add_` update, all particles at once).  Does not synchronise or allocate.
+ * overwritten; G (device, n x D) is read only (App. B.2: the leader's per-pair kernel value and
+ * kernel-gradient accumulation and the followers' parameter update, all particles at once).
+ * Does not synchronise or allocate.
  */
 int svgd_step(svgd_handle_t h, float *X, const float *G, int n, int64_t D, float eps, void *stream);
 
 /*
- * Diagnostic variant of svgd_step: the same kernels, but phi itself is written to PHI
- * (device, n x D) and X is left untouched.
+ * Diagnostic variant of svgd_step: the same kernels, but phi itself - the averaged update vector
+ * that App. B.2's leader sends to each follower - is written to PHI (device, n x D) and X is left
+ * untouched.
  */
 int svgd_phi(svgd_handle_t h, const float *X, const float *G, int n, int64_t D, float *PHI,
              void *stream);
@@ -108,7 +117,7 @@ int svgd_phi(svgd_handle_t h, const float *X, const float *G, int n, int64_t D, 
  * svgd_phi are these with ld = D.  A caller who can choose the layout should make ld a multiple
  * of 32 floats and allocate on a 128-byte boundary: every row then starts on a cache-line
  * boundary, no line is shared by two rows or fetched twice, and the large-n update runs 3-4 %
- * faster than on densely packed rows (paper App. B.2 flattens each particle into a vector of
+ * faster than on densely packed rows (paper App. B.2 gathers each particle into a flat vector of
  * its own; how those vectors are spaced in memory is this library's choice to offer).
  * Carried pair sums (SVGD_FLAG_CARRY_GRAM) are keyed on (X, n, D, ld).
  */
@@ -120,7 +129,8 @@ int svgd_phi_ld(svgd_handle_t h, const float *X, const float *G, int n, int64_t 
                 float *PHI, void *stream);
 
 /*
- * Copy the bandwidth and kernel matrix of the most recent svgd_bandwidth/svgd_step/svgd_phi call
+ * Copy the bandwidth and kernel matrix (App. B.2: the per-pair kernel values, which the paper's
+ * routine reads back one by one) of the most recent svgd_bandwidth/svgd_step/svgd_phi call
  * to HOST memory: *h_out (nullable) receives h; K_host (nullable, row-major) receives K and must
  * have room for n*n floats with the n of that call - the library copies exactly that many and
  * cannot check the buffer.  Synchronises `stream` first.  INVALID_ARG if no step has run yet.
@@ -132,7 +142,8 @@ int svgd_get_last(svgd_handle_t h, double *h_out, float *K_host, void *stream);
  * launched through this handle is bracketed by a pair of HIP events on the stream it is launched
  * on.  svgd_profile_end waits for those events and fills ms_sum[k] / count[k] (HOST arrays of
  * SVGD_KERNEL_KINDS entries) with the total elapsed milliseconds and the number of launches of
- * kernel kind k, then switches recording off.  At most 8192 launches are recorded per session.
+ * kernel kind k, then switches recording off.  At most 2048 launches are recorded per session;
+ * the events are created by svgd_profile_begin*, none while recording.
  * Not every kind runs in every step: a short list of partial sums is reduced inside the
  * BANDWIDTH kernel (no REDUCE launch), carried pair sums replace the GRAM pass, and problems with
  * n <= 8 and n * D <= 16384 run as one kernel, which is counted as UPDATE (as BANDWIDTH when
@@ -150,6 +161,12 @@ int svgd_profile_begin(svgd_handle_t h);
  * costs two event records on the stream, a few microseconds between kernels. */
 int svgd_profile_begin_kinds(svgd_handle_t h, unsigned kinds);
 int svgd_profile_end(svgd_handle_t h, double *ms_sum, int *count);
+/* The same, and the single launches as well: record r < min(rec_cap, launches recorded), in launch
+ * order, puts its kernel kind into rec_kind[r] and its elapsed milliseconds into rec_ms[r] (HOST
+ * arrays of rec_cap entries; may be NULL with rec_cap = 0); *rec_count (nullable) receives the
+ * number of records written. */
+int svgd_profile_end_records(svgd_handle_t h, double *ms_sum, int *count, int *rec_kind, float *rec_ms,
+                             int rec_cap, int *rec_count);
 
 /*
  * Diagnostic: a plain device-to-device copy kernel of nbytes (a multiple of 16; dst and src
@@ -158,6 +175,19 @@ int svgd_profile_end(svgd_handle_t h, double *ms_sum, int *count);
  * other kernels are profiled.
  */
 int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream);
+
+/*
+ * Diagnostic: the memory traffic of the fused update and nothing else - x_i <- x_i + s * g_i in
+ * place for n rows of D floats, ld floats apart (X, G DEVICE pointers as in svgd_step_ld; 12 bytes
+ * moved per element over the same 2n row streams, no kernel matrix, no contraction).  Timing it on
+ * the buffers a benchmark uses gives the rate that this part's memory system sustains for the
+ * update's read-read-write mix, the practical ceiling beside the nominal HBM peak.  `pattern`
+ * 0: a wave instruction covers 4 rows x 256 bytes (the matrix-core update's shape), 1: 1 KiB of
+ * one row (the vector-ALU update's shape); `workgroups` (1..65536) of 256 threads stride over the
+ * column tiles.  Enqueued on `stream` of the current device; does not synchronise or allocate.
+ */
+int svgd_diag_axpy_rows(float *X, const float *G, int n, int64_t D, int64_t ld, float s, int pattern,
+                        int workgroups, void *stream);
 
 /*
  * Multi-SWAG running moments (paper Sec. 2: SWAG keeps the first and second moments of a

@@ -2,7 +2,7 @@
 // matrix K, its row sums, and the coefficient tables of the update kernels.  One workgroup,
 // fp64 throughout (at most 2016 pairs: the cost is nil and none of the 1e-5 budget on h and K
 // is spent here).  Nothing returns to the host: the paper's routine (App. B.2) reads each kernel
-// value back with `.item()`; here K stays on the device.
+// value back to the host, one synchronisation per pair; here K stays on the device.
 #pragma once
 #include "common.hpp"
 

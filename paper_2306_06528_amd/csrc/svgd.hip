@@ -10,6 +10,7 @@
 
 #include "bandwidth_kernels.hpp"
 #include "common.hpp"
+#include "diag_kernels.hpp"
 #include "gram_kernels.hpp"
 #include "swag_kernels.hpp"
 #include "tiny_kernels.hpp"
@@ -39,6 +40,8 @@ struct svgd_ctx {
     int64_t carry_D;
     int64_t carry_ld;
     int carry_nparts;
+    hipStream_t carry_stream; // the stream the carried sums were produced on
+    int64_t partials_cap;     // floats available in `partials`
     int last_n; // 0 = nothing computed yet
     int last_hip_error;
     float *partials;  // [kMaxParts][P]
@@ -90,24 +93,22 @@ int check_handle(svgd_ctx *c)
     return SVGD_OK;
 }
 
-constexpr size_t kMaxProfileRecords = 8192;
+constexpr size_t kMaxProfileRecords = 2048;
 
 // Records a start event on construction and a stop event on destruction when profiling is on.
+// The events come from a pool that svgd_profile_begin* has created: nothing is allocated between
+// the launches that are being timed.
 struct KernelTimer {
     svgd_ctx *c;
     hipStream_t s;
     size_t slot = (size_t)-1;
     KernelTimer(svgd_ctx *ctx, int kind, hipStream_t stream) : c(ctx), s(stream)
     {
-        if (!c->profiling || !((c->profile_kinds >> kind) & 1u) || c->ev_kind.size() >= kMaxProfileRecords) return;
+        if (!c->profiling || !((c->profile_kinds >> kind) & 1u)) return;
         const size_t idx = c->ev_kind.size();
-        while (c->ev_pool.size() < 2 * (idx + 1)) {
-            hipEvent_t e;
-            if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return; }
-            c->ev_pool.push_back(e);
-        }
+        if (idx >= kMaxProfileRecords || c->ev_pool.size() < 2 * (idx + 1)) return;
         if (hipEventRecord(c->ev_pool[2 * idx], s) != hipSuccess) { (void)hipGetLastError(); return; }
-        c->ev_kind.push_back(kind);
+        c->ev_kind.push_back(kind); // capacity reserved by svgd_profile_begin*
         slot = idx;
     }
     ~KernelTimer()
@@ -161,19 +162,30 @@ void launch_update_valu(float *X, const float *G, float *PHI, const float *coef,
     }
 
 int clampi(int64_t v, int lo, int hi) { return (int)(v < lo ? lo : (v > hi ? hi : v)); }
+int mini(int a, int b) { return a < b ? a : b; }
+
+// How many partial vectors of n(n+1)/2 floats the handle's scratch holds: the upper bound on every
+// grid whose workgroups write one partial each.
+int max_parts(const svgd_ctx *c, int n)
+{
+    const int64_t P = (int64_t)n * (n + 1) / 2;
+    const int64_t m = c->partials_cap / P;
+    return (int)(m < kMaxParts ? m : kMaxParts);
+}
 
 // Passes 1 and 2: Gram partials -> fp64 reduction -> h, K, coefficient tables (all on `s`).
 // With use_carry the partials the previous update left in c->partials stand in for pass 1.
 int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld, hipStream_t s, bool use_carry)
 {
     const int P = n * (n + 1) / 2;
+    const int cap_parts = max_parts(c, n);
     int nparts, mode;
     if (use_carry) {
         nparts = c->carry_nparts;
         mode = (n <= 8) ? kModeDiff : kModeGram; // the update kernels mirror the Gram kernels' formats
     } else if (n <= kValuMaxN) {
         const int64_t ngroups = (D + 3) / 4;
-        nparts = clampi((ngroups + 255) / 256, 1, c->num_cu * 3); // all resident at once; each ends with a reduction
+        nparts = clampi((ngroups + 255) / 256, 1, mini(c->num_cu * 3, cap_parts)); // all resident at once; each ends with a reduction
         mode = (n <= 8) ? kModeDiff : kModeGram;
         KernelTimer t(c, SVGD_KERNEL_GRAM, s);
 #define CALL(N) launch_gram_valu<N>(X, D, ld, c->partials, nparts, s)
@@ -182,7 +194,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
     } else {
         KernelTimer t(c, SVGD_KERNEL_GRAM, s);
         const int64_t ntile = (D + 64 * kGramWaves - 1) / (64 * kGramWaves);
-        nparts = clampi(ntile, 1, c->num_cu * 2);
+        nparts = clampi(ntile, 1, mini(c->num_cu * 2, cap_parts));
         mode = kModeGram;
         const int NB = (n + 15) / 16;
         if (NB == 1)
@@ -228,7 +240,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int64_t ngroups = (D + 3) / 4;
         // fewer, longer-lived workgroups when each one ends with a reduction of its pair sums
         const int per_cu = CARRY ? 2 : 8;
-        const int grid = clampi((ngroups + 255) / 256, 1, c->num_cu * per_cu < kMaxParts ? c->num_cu * per_cu : kMaxParts);
+        const int grid = clampi((ngroups + 255) / 256, 1, mini(c->num_cu * per_cu, CARRY ? max_parts(c, n) : kMaxParts));
         if (CARRY) c->carry_nparts = grid;
 #define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, ld, eps, c->partials, grid, s)
         SVGD_SWITCH_N(n, CALL)
@@ -238,7 +250,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int64_t nfull = D / 64;
         // one worker workgroup per CU: the kernel overlaps its own loads with its multiplies, and
         // fewer concurrent row streams keep more HBM pages open
-        const int max_workers = c->num_cu < kMaxParts - 1 ? c->num_cu : kMaxParts - 1;
+        const int max_workers = mini(c->num_cu, (CARRY ? max_parts(c, n) : kMaxParts) - 1);
         const int grid = clampi((nfull + 3) / 4, 1, max_workers) + 1;
         const int NB = (n + 15) / 16;
         if (CARRY) c->carry_nparts = grid; // one partial per workgroup, the tail's included
@@ -294,14 +306,6 @@ int run_tiny(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D
     return SVGD_OK;
 }
 
-// Plain copy of known size: the yardstick against which hardware byte counters are scaled.
-__global__ __launch_bounds__(256) void diag_copy_kernel(const f32x4 *__restrict__ src,
-                                                        f32x4 *__restrict__ dst, int64_t n16)
-{
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (int64_t)gridDim.x * 256)
-        dst[i] = src[i];
-}
-
 } // namespace
 
 extern "C" {
@@ -327,6 +331,8 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
     c->carry_D = 0;
     c->carry_ld = 0;
     c->carry_nparts = 0;
+    c->carry_stream = nullptr;
+    c->partials_cap = 0;
     c->last_n = 0;
     c->last_hip_error = 0;
     c->partials = nullptr;
@@ -366,6 +372,7 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
         delete c;
         return SVGD_ERR_ALLOC;
     }
+    c->partials_cap = (int64_t)kMaxParts * (int64_t)P;
     c->magic = kMagic;
     {
         std::lock_guard<std::mutex> lock(g_live_mutex);
@@ -434,8 +441,10 @@ int svgd_step_ld(svgd_handle_t c, float *X, const float *G, int n, int64_t D, in
     DeviceGuard guard(c->device);
     hipStream_t s = (hipStream_t)stream;
     const bool carry_mode = (c->flags & SVGD_FLAG_CARRY_GRAM) != 0;
+    // the carried sums (and the tables derived from them) were written on carry_stream: a call
+    // on another stream is not ordered after that work and recomputes from X
     const bool use_carry = carry_mode && c->carry_valid && c->carry_X == X && c->carry_n == n &&
-                           c->carry_D == D && c->carry_ld == ld;
+                           c->carry_D == D && c->carry_ld == ld && c->carry_stream == s;
     c->carry_valid = false;
     if (is_tiny(n, D)) return run_tiny<kTinyStep>(c, X, G, nullptr, n, D, ld, eps, s);
     rc = run_kernel_matrix(c, X, n, D, ld, s, use_carry);
@@ -448,6 +457,7 @@ int svgd_step_ld(svgd_handle_t c, float *X, const float *G, int n, int64_t D, in
     c->carry_n = n;
     c->carry_D = D;
     c->carry_ld = ld;
+    c->carry_stream = s;
     return SVGD_OK;
 }
 
@@ -504,6 +514,19 @@ int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream)
     return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
 }
 
+int svgd_diag_axpy_rows(float *X, const float *G, int n, int64_t D, int64_t ld, float s, int pattern,
+                        int workgroups, void *stream)
+{
+    if (!X || !G || n < 1 || D < 1 || ld < D || workgroups < 1 || workgroups > 65536 || (pattern != 0 && pattern != 1))
+        return SVGD_ERR_INVALID_ARG;
+    if (overlaps(X, G, n, D, ld)) return SVGD_ERR_INVALID_ARG;
+    if (pattern == 0)
+        diag_axpy_rows_kernel<0><<<workgroups, 256, 0, (hipStream_t)stream>>>(X, G, n, D, ld, s);
+    else
+        diag_axpy_rows_kernel<1><<<workgroups, 256, 0, (hipStream_t)stream>>>(X, G, n, D, ld, s);
+    return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
+}
+
 int swag_update_moments(float *mean, float *sqmean, const float *X, int n, int64_t D, int64_t count,
                         void *stream)
 {
@@ -527,6 +550,21 @@ int svgd_profile_begin_kinds(svgd_handle_t c, unsigned kinds)
     int rc = check_handle(c);
     if (rc) return rc;
     if ((kinds & ((1u << SVGD_KERNEL_KINDS) - 1u)) == 0) return SVGD_ERR_INVALID_ARG;
+    {   // all events and the record list exist before the first timed launch
+        DeviceGuard guard(c->device);
+        try {
+            c->ev_kind.reserve(kMaxProfileRecords);
+            c->ev_pool.reserve(2 * kMaxProfileRecords);
+        } catch (...) {
+            return SVGD_ERR_ALLOC;
+        }
+        while (c->ev_pool.size() < 2 * kMaxProfileRecords) {
+            hipEvent_t e;
+            hipError_t rc_e = hipEventCreate(&e);
+            if (rc_e != hipSuccess) return fail(c, rc_e);
+            c->ev_pool.push_back(e);
+        }
+    }
     c->ev_kind.clear();
     c->profile_kinds = kinds;
     c->profiling = true;
@@ -535,13 +573,15 @@ int svgd_profile_begin_kinds(svgd_handle_t c, unsigned kinds)
 
 int svgd_profile_begin(svgd_handle_t c) { return svgd_profile_begin_kinds(c, ~0u); }
 
-int svgd_profile_end(svgd_handle_t c, double *ms_sum, int *count)
+int svgd_profile_end_records(svgd_handle_t c, double *ms_sum, int *count, int *rec_kind, float *rec_ms,
+                             int rec_cap, int *rec_count)
 {
     int rc = check_handle(c);
     if (rc) return rc;
-    if (!ms_sum || !count) return SVGD_ERR_INVALID_ARG;
+    if (!ms_sum || !count || rec_cap < 0 || (rec_cap > 0 && (!rec_kind || !rec_ms))) return SVGD_ERR_INVALID_ARG;
     c->profiling = false;
     for (int k = 0; k < SVGD_KERNEL_KINDS; ++k) { ms_sum[k] = 0.0; count[k] = 0; }
+    if (rec_count) *rec_count = 0;
     DeviceGuard guard(c->device);
     for (size_t r = 0; r < c->ev_kind.size(); ++r) {
         hipError_t e = hipEventSynchronize(c->ev_pool[2 * r + 1]);
@@ -550,9 +590,19 @@ int svgd_profile_end(svgd_handle_t c, double *ms_sum, int *count)
         if (e != hipSuccess) { c->ev_kind.clear(); return fail(c, e); }
         ms_sum[c->ev_kind[r]] += (double)ms;
         count[c->ev_kind[r]] += 1;
+        if ((int)r < rec_cap) {
+            rec_kind[r] = c->ev_kind[r];
+            rec_ms[r] = ms;
+            if (rec_count) *rec_count = (int)r + 1;
+        }
     }
     c->ev_kind.clear();
     return SVGD_OK;
+}
+
+int svgd_profile_end(svgd_handle_t c, double *ms_sum, int *count)
+{
+    return svgd_profile_end_records(c, ms_sum, count, nullptr, nullptr, 0, nullptr);
 }
 
 int svgd_destroy(svgd_handle_t c)

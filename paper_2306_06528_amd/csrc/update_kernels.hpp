@@ -5,8 +5,9 @@
 //     x_ik  <- x_ik + eps * phi_ik
 //
 // which is phi_i = (1/n) sum_j [K_ij g_j + (2/h) K_ij (x_i - x_j)] with the sum over j of the
-// x_j terms folded into a single n x n product (paper App. B.2: `update.add_(p_j_grad, alpha=k)`,
-// `update.add_(diff)`, `update / n`, then the followers' `p.add_(update, alpha=lr)`).
+// x_j terms folded into a single n x n product (paper App. B.2, SVGD routine: per-pair kernel value,
+// accumulation of the kernel-weighted gradients and of the kernel gradient, division by n, then
+// the followers' parameter update; here in the score/ascent convention, x += eps * phi).
 // X and G are read once and X is written once, in place: a column's outputs depend only on that
 // column's inputs, and every thread/wave loads all n rows of its columns before storing any, so
 // every phi_i is computed from the pre-step X.

@@ -38,6 +38,9 @@ _lib.svgd_get_last.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.c_voi
 _lib.svgd_destroy.argtypes = [_H]
 _lib.svgd_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
 _lib.svgd_diag_copy.restype = ctypes.c_int
+_lib.svgd_diag_axpy_rows.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                     ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+_lib.svgd_diag_axpy_rows.restype = ctypes.c_int
 _lib.swag_update_moments.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                      ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p]
 _lib.swag_update_moments.restype = ctypes.c_int
@@ -45,6 +48,10 @@ _lib.svgd_profile_begin.argtypes = [_H]
 _lib.svgd_profile_begin_kinds.argtypes = [_H, ctypes.c_uint]
 _lib.svgd_profile_begin_kinds.restype = ctypes.c_int
 _lib.svgd_profile_end.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
+_lib.svgd_profile_end_records.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int),
+                                          ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_float),
+                                          ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
+_lib.svgd_profile_end_records.restype = ctypes.c_int
 _lib.svgd_last_device_error.argtypes = [_H]
 _lib.svgd_status_string.argtypes = [ctypes.c_int]
 _lib.svgd_status_string.restype = ctypes.c_char_p
@@ -101,6 +108,29 @@ def diag_copy(dst: torch.Tensor, src: torch.Tensor, stream=None):
     if dst.numel() * dst.element_size() != nbytes:
         raise ValueError("dst and src must have the same size in bytes")
     rc = _lib.svgd_diag_copy(dst.data_ptr(), src.data_ptr(), nbytes, _stream_ptr(stream))
+    if rc != SVGD_OK:
+        raise SvgdError(rc)
+
+
+def _rows_of(t, name):
+    """(n, D, ld) of a 2-D float32 CUDA tensor with contiguous rows."""
+    if not isinstance(t, torch.Tensor) or t.dtype is not torch.float32 or not t.is_cuda or t.dim() != 2:
+        raise TypeError(f"{name} must be a 2-D float32 CUDA tensor")
+    (n, D), st = t.shape, t.stride()
+    if (D != 1 and st[1] != 1) or (n != 1 and st[0] < D):
+        raise TypeError(f"{name} must have contiguous rows, at least D elements apart")
+    return n, D, (st[0] if n != 1 else D)
+
+
+def diag_axpy_rows(X: torch.Tensor, G: torch.Tensor, s: float, pattern: int, workgroups: int, stream=None):
+    """Plain in-place X += s * G over the row streams of X and G (the update's memory traffic and
+    nothing else; see svgd_diag_axpy_rows)."""
+    shape = _rows_of(X, "X")
+    if _rows_of(G, "G") != shape:
+        raise ValueError("G must have the shape and row stride of X")
+    n, D, ld = shape
+    rc = _lib.svgd_diag_axpy_rows(X.data_ptr(), G.data_ptr(), n, D, ld, float(s), int(pattern), int(workgroups),
+                                  _stream_ptr(stream))
     if rc != SVGD_OK:
         raise SvgdError(rc)
 
@@ -211,6 +241,17 @@ class Svgd:
         cnt = (ctypes.c_int * 4)()
         self._check(_lib.svgd_profile_end(self._h, ms, cnt))
         return {k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_KINDS)}
+
+    def profile_end_records(self, cap: int = 2048):
+        """({kind: (total_ms, launches)}, [(kind, ms) per launch, in launch order])."""
+        ms = (ctypes.c_double * 4)()
+        cnt = (ctypes.c_int * 4)()
+        rk = (ctypes.c_int * cap)()
+        rm = (ctypes.c_float * cap)()
+        nrec = ctypes.c_int(0)
+        self._check(_lib.svgd_profile_end_records(self._h, ms, cnt, rk, rm, cap, ctypes.byref(nrec)))
+        return ({k: (ms[i], cnt[i]) for i, k in enumerate(KERNEL_KINDS)},
+                [(KERNEL_KINDS[rk[r]], rm[r]) for r in range(nrec.value)])
 
     def close(self):
         if self._h:

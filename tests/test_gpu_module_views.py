@@ -12,6 +12,7 @@ import pytest
 import torch
 
 from oracle import svgd_oracle as orc
+from parity_checks import assert_x_new
 
 pytestmark = pytest.mark.gpu
 
@@ -79,8 +80,7 @@ def test_modules_as_views_of_the_particle_matrix(width):
             ref = orc.step(Xh, Gh, eps)
             assert abs(h - ref["h"]) / ref["h"] <= TOL_H, f"step {step}"
             assert np.abs(K - ref["K"]).max() <= TOL_K, f"step {step}"
-            err = np.abs(X.cpu().numpy() - ref["X_new"]).max() / np.abs(ref["X_new"]).max()
-            assert err <= 1e-6, f"step {step}: {err:.3e}"
+            assert_x_new(X.cpu().numpy(), ref, eps, f"step {step}")
     # the networks saw the update: their parameters are X, and the posterior went up
     for i, net in enumerate(nets):
         flat = torch.cat([p.data.reshape(-1) for p in net.parameters()])

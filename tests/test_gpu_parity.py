@@ -13,10 +13,10 @@ import torch
 
 from oracle import svgd_oracle as orc
 from paper_2306_06528_amd import workloads
+from parity_checks import (TOL_PHI, TOL_H, TOL_K, assert_x_new, check_carried_chain, oracle_kernel_matrix,
+                           padded_copy, phi_error_all_columns, ulp_diff as _ulp_diff, ulp_diff_device)
 
 pytestmark = pytest.mark.gpu
-
-TOL_PHI, TOL_H, TOL_K = 1e-4, 1e-5, 1e-5
 
 
 @pytest.fixture(scope="module")
@@ -24,14 +24,6 @@ def svgd():
     assert torch.cuda.is_available(), "these tests need the GPU"
     from paper_2306_06528_amd import svgd as mod   # raises if libsvgd.so is missing
     return mod
-
-
-def _ulp_diff(a, b):
-    """max distance in units of fp32 ulp of b."""
-    a = a.astype(np.float64)
-    b32 = b.astype(np.float32)
-    ulp = np.spacing(np.abs(b32)).astype(np.float64)
-    return float((np.abs(a - b32.astype(np.float64)) / ulp).max())
 
 
 def check_one_step(svgd, X0, G, eps, h_fixed=0.0, tol_phi=TOL_PHI):
@@ -116,8 +108,7 @@ def test_single_launch_and_carried_sums_do_not_mix(svgd):
             ref = orc.step(Xh, G.cpu().numpy(), 0.05)
             assert abs(h - ref["h"]) / ref["h"] <= TOL_H
             assert np.abs(K - ref["K"]).max() <= TOL_K
-            err = np.abs(X.cpu().numpy() - ref["X_new"]).max() / np.abs(ref["X_new"]).max()
-            assert err <= 1e-6
+            assert_x_new(X.cpu().numpy(), ref, 0.05, f"n={n}")
 
 
 @pytest.mark.parametrize("n", [1, 2, 4, 8, 13, 16, 20, 32, 40, 64])
@@ -230,8 +221,7 @@ def test_stream_argument(svgd):
             eng.step(X, G, 0.01, stream=s)
         s.synchronize()
     ref = orc.step(X0.cpu().numpy(), G.cpu().numpy(), 0.01)
-    err = np.abs(X.cpu().numpy() - ref["X_new"]).max() / np.abs(ref["X_new"]).max()
-    assert err <= 1e-6
+    assert_x_new(X.cpu().numpy(), ref, 0.01)
 
 
 # ----------------------------------------------------------------------------------------------
@@ -294,9 +284,11 @@ def test_config2_pinn_mlp_trajectory(svgd):
                     assert drift <= 1e-4, f"free-running drift after 100 steps {drift:.3e}"
 
 
-def _full_size_check(svgd, cfg_index, nchunks=6, chunk=4096):
-    """Full-size config in the launch configuration the benchmark times: h and K against the
-    oracle's full d2; phi on sampled column chunks (start, middle, ragged end)."""
+def _full_size_check(svgd, cfg_index):
+    """Full-size config, dense rows, plain handle (the four-kernel step of the four-call ABI): h and
+    K against the oracle's full d2, phi on ALL columns against the oracle (streamed in chunks, the
+    normaliser is the oracle's max|phi|), and the in-place update == fl32(x + eps * phi_gpu) to one
+    ulp on all n * D entries."""
     wl = workloads.make(cfg_index, device="cuda")
     n, D = wl.n, wl.D
     X = wl.X0.clone()
@@ -308,31 +300,13 @@ def _full_size_check(svgd, cfg_index, nchunks=6, chunk=4096):
         eng.step(X, G, wl.cfg.eps)
         torch.cuda.synchronize()
     Xh, Gh = wl.X0.cpu().numpy(), G.cpu().numpy()
-    d2 = orc.pairwise_d2(Xh)
-    h_ref = orc.bandwidth(d2)
-    K_ref, _ = orc.kernel(d2, h_ref)
+    h_ref, K_ref = oracle_kernel_matrix(Xh)
     assert abs(h - h_ref) / h_ref <= TOL_H, f"h {h} vs {h_ref}"
     assert np.abs(K - K_ref).max() <= TOL_K
-    rng = np.random.default_rng(cfg_index)
-    starts = [0, D - chunk] + [int(s) for s in rng.integers(0, D - chunk, nchunks - 2)]
-    # max|phi| over the whole array from the GPU result (it is only the normaliser)
-    scale = float(PHI.abs().max().item())
-    Xn = X.cpu().numpy()
-    PHIh = PHI.cpu().numpy()
-    worst = 0.0
-    for s in starts:
-        ref = orc.phi_cols(Xh, Gh, K_ref, h_ref, s, chunk)
-        got = PHIh[:, s:s + chunk].astype(np.float64)
-        worst = max(worst, np.abs(got - ref).max() / scale)
-        assert np.abs(got - ref).max() / np.abs(ref).max() <= TOL_PHI * 10  # chunk-local sanity
-        want = Xh[:, s:s + chunk].astype(np.float64) + np.float64(np.float32(wl.cfg.eps)) * got
-        assert _ulp_diff(want, Xn[:, s:s + chunk]) <= 1.0
-    assert worst <= TOL_PHI, f"phi err / max|phi| = {worst:.3e}"
-    # properties that hold at any size: columns are independent, so the whole update equals
-    # x + eps*phi everywhere (checked on the device, all n*D entries)
-    want_all = torch.addcmul(wl.X0.double(), PHI.double(),
-                             torch.tensor(float(np.float32(wl.cfg.eps)), device="cuda", dtype=torch.float64))
-    assert (X.double() - want_all).abs().max().item() <= 2.0 * float(np.spacing(np.float32(wl.X0.abs().max().item())))
+    e_phi = phi_error_all_columns(PHI, Xh, Gh, K_ref, h_ref)
+    assert e_phi <= TOL_PHI, f"phi err / max|phi| = {e_phi:.3e}"
+    ulps = ulp_diff_device(X, wl.X0, PHI, wl.cfg.eps)
+    assert ulps <= 1.0, f"in-place update differs from x + eps*phi_gpu by {ulps} ulp"
 
 
 def test_config3_operator_net_full_size(svgd):
@@ -385,8 +359,7 @@ def test_rows_with_a_leading_dimension(svgd, n, D, ld, carry):
             r = orc.step(Xh, G0.cpu().numpy(), eps)
             assert abs(h - r["h"]) / r["h"] <= TOL_H, f"step {step}"
             assert np.abs(K - r["K"]).max() <= TOL_K, f"step {step}"
-            err = np.abs(X.cpu().numpy() - r["X_new"]).max() / np.abs(r["X_new"]).max()
-            assert err <= 1e-6, f"step {step}: {err:.3e}"
+            assert_x_new(X.cpu().numpy(), r, eps, f"step {step}")
     if ld > D:
         assert torch.isnan(Xb[:, D:]).all() and torch.isnan(Gb[:, D:]).all(), "padding of X or G was written"
         assert torch.all(Pb[:, D:] == 7.0), "padding of PHI was written"
@@ -406,71 +379,79 @@ def test_mixed_leading_dimensions_are_rejected(svgd):
     eng.close()
 
 
-@pytest.mark.parametrize("n,D,carry", [(3, 800_000_001, True), (16, 150_000_001, False), (64, 34_000_001, True)])
-def test_more_than_2_to_31_elements(svgd, n, D, carry):
+@pytest.mark.parametrize("n,D,carry,padded", [(3, 800_000_001, True, False), (16, 150_000_001, False, False),
+                                              (64, 34_000_001, True, False), (64, 34_000_001, True, True)])
+def test_more_than_2_to_31_elements(svgd, n, D, carry, padded):
     """n * D = 2.4e9 elements (9.6 GB per array): element offsets beyond 32 bits on the vector-ALU
-    and on the matrix-core path.  h and K against the oracle's full pass; phi and the in-place
-    update on column chunks at both ends and around element offset 2^31."""
+    and on the matrix-core path, dense rows and rows padded to 128 bytes.  h and K against the
+    oracle's full pass; phi on column chunks at both ends and around element offset 2^31 (normalised
+    by the oracle's maximum over those chunks); the in-place update == fl32(x + eps * phi_gpu) to one
+    ulp on ALL entries, for the first step and (carry) for the second, which runs on carried sums."""
     assert n * D > 2 ** 31
     chunk = 4096
     g = torch.Generator(device="cuda")
     g.manual_seed(5 * n + 1)
     X = torch.randn(n, D, generator=g, device="cuda") * 0.02
     G = torch.randn(n, D, generator=g, device="cuda") * 1e-3
+    if padded:
+        Xd, Gd = X, G
+        X, G = padded_copy(svgd, Xd), padded_copy(svgd, Gd)
+        del Xd, Gd
+        PHI = svgd.padded_rows(n, D)
+    else:
+        PHI = torch.empty_like(X)
     eps = 1e-3
     cross = (2 ** 31) % D   # a column at which some row's element offset passes 2^31
     starts = sorted({0, D - chunk, min(max(cross - chunk // 2, 0), D - chunk), D // 2 + 7})
-    Xh = X.cpu().numpy()
     G_chunks = {s0: G[:, s0:s0 + chunk].cpu().numpy() for s0 in starts}
-    PHI = torch.empty_like(X)
-    with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM if carry else 0) as eng:
+
+    def check_phi_chunks(Xh, h_ref, K_ref, what):
+        refs = {s0: orc.phi_cols(np.ascontiguousarray(Xh[:, s0:s0 + chunk]), G_chunks[s0], K_ref, h_ref, 0, chunk)
+                for s0 in starts}
+        scale = max(float(np.abs(r).max()) for r in refs.values())
+        for s0, ref in refs.items():
+            got = PHI[:, s0:s0 + chunk].cpu().numpy().astype(np.float64)
+            assert np.abs(got - ref).max() / scale <= TOL_PHI, f"{what}: chunk at {s0}"
+
+    with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM if carry else 0) as eng, svgd.Svgd(n, D) as plain:
+        X_old = X.clone()
         eng.phi(X, G, PHI)
         h, K = eng.get_last(n)
         eng.step(X, G, eps)
-        torch.cuda.synchronize()
-        d2 = orc.pairwise_d2(Xh)
-        h_ref = orc.bandwidth(d2)
-        K_ref, _ = orc.kernel(d2, h_ref)
+        Xh = X_old.cpu().numpy()
+        h_ref, K_ref = oracle_kernel_matrix(Xh)
         assert abs(h - h_ref) / h_ref <= TOL_H, f"h {h} vs {h_ref}"
         assert np.abs(K - K_ref).max() <= TOL_K
-        scale = float(PHI.abs().max().item())
-        for s0 in starts:
-            # phi_cols reads whole rows of X and G: give it G rows that are right on this chunk
-            ref = orc.phi_cols(Xh[:, s0:s0 + chunk], G_chunks[s0], K_ref, h_ref, 0, chunk)
-            got = PHI[:, s0:s0 + chunk].cpu().numpy().astype(np.float64)
-            assert np.abs(got - ref).max() / scale <= TOL_PHI, f"chunk at {s0}"
-            want = Xh[:, s0:s0 + chunk].astype(np.float64) + np.float64(np.float32(eps)) * got
-            assert _ulp_diff(want, X[:, s0:s0 + chunk].cpu().numpy()) <= 1.0, f"chunk at {s0}"
+        check_phi_chunks(Xh, h_ref, K_ref, "step 0")
+        assert ulp_diff_device(X, X_old, PHI, eps) <= 1.0
+        del Xh
         if carry:   # the next step takes its pair sums from the update that just ran
-            X1h = X.cpu().numpy()
+            X_old.copy_(X)
+            plain.phi(X, G, PHI)
             eng.step(X, G, eps)
             h2, K2 = eng.get_last(n)
-            d2 = orc.pairwise_d2(X1h)
-            h2_ref = orc.bandwidth(d2)
+            X1h = X_old.cpu().numpy()
+            h2_ref, K2_ref = oracle_kernel_matrix(X1h)
             assert abs(h2 - h2_ref) / h2_ref <= TOL_H
-            assert np.abs(K2 - orc.kernel(d2, h2_ref)[0]).max() <= TOL_K
+            assert np.abs(K2 - K2_ref).max() <= TOL_K
+            check_phi_chunks(X1h, h2_ref, K2_ref, "step 1")
+            assert ulp_diff_device(X, X_old, PHI, eps) <= 1.0
 
 
 # ----------------------------------------------------------------------------------------------
 # carried Gram (SVGD_FLAG_CARRY_GRAM): step t's update also accumulates the pair sums of the new
 # X, and step t+1 skips its own pass over X
 # ----------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("padded", [False, True])
 @pytest.mark.parametrize("n,D", [(64, 70_001), (32, 4096), (17, 1531), (48, 129), (33, 200_000), (64, 63),
                                  (8, 100_003), (4, 1024), (16, 8577), (12, 70_001), (1, 100), (2, 65),
-                                 (8, 3_000_017)])
-def test_carried_gram_matches_oracle_every_step(svgd, n, D):
+                                 (8, 3_000_017), (16, 70_001), (48, 20_011), (49, 5003)])
+def test_carried_gram_matches_oracle_every_step(svgd, n, D, padded):
+    """Four steps in a row with carried pair sums, on dense rows and on rows padded to 128 bytes
+    (the layout that selects the direct-store instance of the matrix-core update kernel): h, K,
+    phi against the oracle and X_new == fl32(x + eps * phi_gpu) to one ulp, every step."""
     X, G = _random_problem(n, D, 31 * n + D, x_std=0.3)
-    eps = 0.05
-    with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM) as eng:
-        for step in range(4):
-            Xh = X.cpu().numpy()
-            eng.step(X, G, eps)           # steps 1.. use the sums carried from the previous step
-            h, K = eng.get_last(n)
-            ref = orc.step(Xh, G.cpu().numpy(), eps)
-            assert abs(h - ref["h"]) / ref["h"] <= TOL_H, f"step {step}: h {h} vs {ref['h']}"
-            assert np.abs(K - ref["K"]).max() <= TOL_K, f"step {step}"
-            err = np.abs(X.cpu().numpy() - ref["X_new"]).max() / np.abs(ref["X_new"]).max()
-            assert err <= 1e-6, f"step {step}: X err {err:.3e}"
+    check_carried_chain(svgd, X, G, 0.05, padded=padded, steps=4)
 
 
 def test_carried_gram_is_dropped_when_it_must_be(svgd):
@@ -500,33 +481,43 @@ def test_carried_gram_is_dropped_when_it_must_be(svgd):
         assert abs(h3 - orc.step(X2h, G.cpu().numpy(), 0.01, want_phi=False, want_xnew=False)["h"]) / h3 <= TOL_H
 
 
-@pytest.mark.parametrize("cfg_index", [3, 4, 5])
-def test_full_size_carried_gram(svgd, cfg_index):
-    """Full-size configs in the launch configuration the benchmark times (pair sums carried from
-    the previous update): h and K of the second step against the oracle, X on sampled chunks."""
-    wl = workloads.make(cfg_index, device="cuda")
-    n, D = wl.n, wl.D
-    X = wl.X0.clone()
-    G = wl.score(X, 0)
+def test_carried_gram_is_dropped_on_another_stream(svgd):
+    """The carried sums were written on the stream of the step that produced them; a step on another
+    stream is not ordered behind that work, so it runs its own pass over X (seen as a launch of the
+    pairwise-d2 kernel) - and its result is right."""
+    n, D = 32, 50_021
+    X, G = _random_problem(n, D, 78, x_std=0.3)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM) as eng:
-        eng.step(X, G, wl.cfg.eps)
-        X1 = X.cpu().numpy()
-        eng.step(X, G, wl.cfg.eps)
-        h, K = eng.get_last(n)
         torch.cuda.synchronize()
-    d2 = orc.pairwise_d2(X1)
-    h_ref = orc.bandwidth(d2)
-    K_ref, _ = orc.kernel(d2, h_ref)
-    assert abs(h - h_ref) / h_ref <= TOL_H
-    assert np.abs(K - K_ref).max() <= TOL_K
-    rng = np.random.default_rng(cfg_index)
-    Gh = G.cpu().numpy()
-    X2 = X.cpu().numpy()
-    for s in [0, D - 4096] + [int(v) for v in rng.integers(0, D - 4096, 3)]:
-        phi = orc.phi_cols(X1, Gh, K_ref, h_ref, s, 4096)
-        want = X1[:, s:s + 4096].astype(np.float64) + wl.cfg.eps * phi
-        err = np.abs(X2[:, s:s + 4096] - want).max() / np.abs(want).max()
-        assert err <= 1e-6
+        eng.profile_begin()
+        eng.step(X, G, 0.01, stream=s1)
+        eng.step(X, G, 0.01, stream=s1)      # same stream: carried sums, no pass over X
+        s1.synchronize()
+        Xh = X.cpu().numpy()
+        eng.step(X, G, 0.01, stream=s2)      # other stream: recomputed
+        s2.synchronize()
+        h, K = eng.get_last(n, stream=s2)
+        prof = eng.profile_end()
+    assert prof["gram"][1] == 2 and prof["update"][1] == 3
+    ref = orc.step(Xh, G.cpu().numpy(), 0.01)
+    assert abs(h - ref["h"]) / ref["h"] <= TOL_H
+    assert np.abs(K - ref["K"]).max() <= TOL_K
+    assert_x_new(X.cpu().numpy(), ref, 0.01)
+
+
+@pytest.mark.parametrize("padded", [True, False])
+@pytest.mark.parametrize("cfg_index", [3, 4, 5])
+def test_full_size_carried_gram(svgd, cfg_index, padded):
+    """Full-size configs in the launch configurations the benchmark times: pair sums carried from
+    the previous update, rows padded to 128 bytes (the headline; at config 5 this is the instance
+    update_mfma_kernel<4, false, true, true, true>) and dense rows.  Two steps, the second on carried
+    sums; each step: h and K against the oracle, phi of ALL columns against the oracle at 1e-4 of
+    max|phi|, X_new == fl32(x + eps * phi_gpu) to one ulp on all n * D entries."""
+    wl = workloads.make(cfg_index, device="cuda")
+    X0 = wl.X0
+    G = wl.score(X0, 0)
+    check_carried_chain(svgd, X0, G, wl.cfg.eps, padded=padded, steps=2)
 
 
 @pytest.mark.parametrize("n", [8, 32, 64])
@@ -554,8 +545,7 @@ def test_buffers_with_odd_base_alignment(svgd, n, shift):
             torch.cuda.synchronize()
         e = np.abs(PHI.cpu().numpy() - ref["phi"]).max() / np.abs(ref["phi"]).max()
         assert e <= TOL_PHI
-        err = np.abs(Xw.cpu().numpy() - ref["X_new"]).max() / np.abs(ref["X_new"]).max()
-        assert err <= 1e-6
+        assert_x_new(Xw.cpu().numpy(), ref, 0.01, f"flags={flags}")
         # nothing outside the n*D window was touched
         base = Xw._base if Xw._base is not None else Xw
         flat = base.view(-1)
