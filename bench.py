@@ -151,6 +151,7 @@ def main():
                     help="rows D floats apart (ld = D) instead of ld = D rounded up to 32 floats")
     ap.add_argument("--swag", action="store_true",
                     help="time the multi-SWAG running-moments kernel on the config's n x D instead of svgd_step")
+    ap.add_argument("--verbose", action="store_true", help="print the yardstick sweep to stderr")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the plain copy kernel once over G (for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
@@ -236,7 +237,7 @@ def main():
         best = None
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         reps = 10
-        for pattern in (0, 1):
+        for pattern in (0, 1, 2, 3):
             for per_cu in (1, 2, 4, 8):
                 for _ in range(3):
                     svgd.diag_axpy_rows(Xv, Gv, 0.0, pattern, cus * per_cu, stream=stream)
@@ -247,6 +248,8 @@ def main():
                 torch.cuda.synchronize()
                 ms = e0.elapsed_time(e1) / reps
                 gbs = UPDATE_BYTES_PER_PARAM * n * D / (ms * 1e-3) / 1e9
+                if args.verbose:
+                    print(f"axpy_rows pattern {pattern} x {per_cu}/CU: {ms:.4f} ms {gbs:.0f} GB/s", file=sys.stderr)
                 if best is None or gbs > best["gbs"]:
                     best = {"gbs": gbs, "ms": ms, "pattern": pattern, "workgroups": cus * per_cu}
         return best

@@ -18,39 +18,49 @@ __global__ __launch_bounds__(256) void diag_copy_kernel(const f32x4 *__restrict_
 // of D floats, ld floats apart - per element one read of X, one read of G, one write of X, over
 // the same 2n row streams, with 16-byte accesses.  No kernel matrix, no contraction.
 //   PAT 0: the matrix-core update's access pattern - a wave instruction covers 4 rows x 256 bytes
-//          (lane (q, c) takes row r0 + q of a 64-column tile), 8 such loads per array in flight;
+//          (lane (q, c) takes row r0 + q of a 64-column tile);
 //   PAT 1: the vector-ALU update's pattern - a wave instruction covers 1 KiB of one row (256-column
-//          tile), 8 rows per array in flight.
-// The waves of a workgroup take adjacent tiles; workgroups stride over the tiles.  Stores carry
-// the streaming hint, as the update's do.
-template <int PAT>
+//          tile).
+// U loads per array are in flight per lane (U * RPI rows); rows beyond n are clamped for the loads
+// and masked for the stores, so the steady state has no divergent branch.  The waves of a
+// workgroup take adjacent tiles; workgroups stride over the full tiles; the columns after the
+// last full tile are done element-wise by the last workgroup.  Stores carry the streaming hint,
+// as the update's do.
+template <int PAT, int U>
 __global__ __launch_bounds__(256) void diag_axpy_rows_kernel(float *__restrict__ X, const float *__restrict__ G,
                                                              int n, int64_t D, int64_t ld, float s)
 {
     constexpr int TC = PAT == 0 ? 64 : 256;      // columns per wave tile
     constexpr int RPI = PAT == 0 ? 4 : 1;        // rows per wave instruction
-    constexpr int U = 8;                         // loads per array in flight
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = lane >> 4, c16 = lane & 15;
-    const int64_t ntile = (D + TC - 1) / TC;
-    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < ntile; tile += (int64_t)gridDim.x * 4) {
-        const int64_t col = tile * TC + (PAT == 0 ? 4 * c16 : 4 * lane);
-        const bool full = (col + 4 <= D);
+    const int64_t nfull = D / TC;
+    const int lrow = PAT == 0 ? q : 0;
+    const int64_t lcol = PAT == 0 ? 4 * c16 : 4 * lane;
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < nfull; tile += (int64_t)gridDim.x * 4) {
+        const int64_t col = tile * TC + lcol;
         for (int r0 = 0; r0 < n; r0 += U * RPI) {
             f32x4 x[U], g[U];
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int row = r0 + u * RPI + (PAT == 0 ? q : 0);
-                if (row < n) {
-                    x[u] = load4(X + (int64_t)row * ld, col, D, full);
-                    g[u] = load4(G + (int64_t)row * ld, col, D, full);
-                }
+                const int row = r0 + u * RPI + lrow;
+                const int64_t off = (int64_t)(row < n ? row : n - 1) * ld + col;
+                x[u] = *reinterpret_cast<const f32x4u *>(X + off);
+                g[u] = *reinterpret_cast<const f32x4u *>(G + off);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {
-                const int row = r0 + u * RPI + (PAT == 0 ? q : 0);
-                if (row < n) store4(X + (int64_t)row * ld, col, D, full, x[u] + s * g[u]);
+                const int row = r0 + u * RPI + lrow;
+                if (row < n)
+                    __builtin_nontemporal_store(x[u] + s * g[u], reinterpret_cast<f32x4u *>(X + (int64_t)row * ld + col));
             }
+        }
+    }
+    if (blockIdx.x == gridDim.x - 1) {
+        const int64_t c0 = nfull * TC, ntail = D - c0;
+        for (int64_t e = threadIdx.x; e < ntail * n; e += 256) {
+            const int64_t row = e / ntail, col = c0 + e % ntail;
+            X[row * ld + col] += s * G[row * ld + col];
         }
     }
 }

@@ -517,13 +517,16 @@ int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream)
 int svgd_diag_axpy_rows(float *X, const float *G, int n, int64_t D, int64_t ld, float s, int pattern,
                         int workgroups, void *stream)
 {
-    if (!X || !G || n < 1 || D < 1 || ld < D || workgroups < 1 || workgroups > 65536 || (pattern != 0 && pattern != 1))
+    if (!X || !G || n < 1 || D < 1 || ld < D || workgroups < 1 || workgroups > 65536 || pattern < 0 || pattern > 3)
         return SVGD_ERR_INVALID_ARG;
     if (overlaps(X, G, n, D, ld)) return SVGD_ERR_INVALID_ARG;
-    if (pattern == 0)
-        diag_axpy_rows_kernel<0><<<workgroups, 256, 0, (hipStream_t)stream>>>(X, G, n, D, ld, s);
-    else
-        diag_axpy_rows_kernel<1><<<workgroups, 256, 0, (hipStream_t)stream>>>(X, G, n, D, ld, s);
+    hipStream_t st = (hipStream_t)stream;
+    switch (pattern) {
+    case 0: diag_axpy_rows_kernel<0, 8><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    case 1: diag_axpy_rows_kernel<1, 8><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    case 2: diag_axpy_rows_kernel<0, 16><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    default: diag_axpy_rows_kernel<1, 16><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    }
     return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
 }
 
