@@ -203,6 +203,24 @@ int svgd_diag_axpy_rows(float *X, const float *G, int n, int64_t D, int64_t ld, 
 int swag_update_moments(float *mean, float *sqmean, const float *X, int n, int64_t D, int64_t count,
                         void *stream);
 
+/*
+ * svgd_step_ld for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  No handle: the scratch (partial sums, their reduction,
+ * h, K and the coefficient tables, 4.3 MB) is a static device array inside the library, one copy
+ * per GPU, held until the process ends.  Plain step on the current device: median-heuristic
+ * bandwidth, pair sums recomputed from X every call (nothing is carried), X updated in place;
+ * same kernels and results as svgd_step_ld on a handle created with flags = 0.  Calls no
+ * hipMalloc/hipFree or any other allocating routine and does not synchronise; the first call on
+ * a device looks up the array's device address (make that call outside graph capture).
+ * Limits: n <= SVGD_MAX_PARTICLES, D <= SVGD_STATIC_MAX_D, else SVGD_ERR_TOO_LARGE.  Every call
+ * on one GPU uses the same scratch, which keeps the previous call's contents (each call
+ * overwrites what it reads; nothing needs clearing): calls that overlap in time on one GPU -
+ * different streams without ordering between them, several host threads - race.  Other errors as
+ * svgd_step_ld.
+ */
+#define SVGD_STATIC_MAX_D ((int64_t)1 << 32)
+int svgd_step_static(float *X, const float *G, int n, int64_t D, int64_t ld, float eps, void *stream);
+
 /* Free the handle's scratch and invalidate the handle.  The caller synchronises beforehand. */
 int svgd_destroy(svgd_handle_t h);
 

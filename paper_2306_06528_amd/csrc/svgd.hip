@@ -306,6 +306,80 @@ int run_tiny(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D
     return SVGD_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// The entry point that allocates nothing: its scratch is a file-scope device array, one copy per
+// GPU, resolved to a device address once per device.
+// ---------------------------------------------------------------------------------------------
+constexpr int kStaticMaxParts = 512;                         // partial vectors of n(n+1)/2 <= 2080 floats
+constexpr size_t kStaticPartialsBytes = (size_t)kStaticMaxParts * kMaxPairsFull * sizeof(float);
+constexpr size_t kStaticPart2Bytes = (size_t)kSlices * kMaxPairsFull * sizeof(double);
+constexpr size_t kStaticCoefBytes = (size_t)kCoefFloats * sizeof(float);
+constexpr size_t kStaticStateBytes = 256;
+constexpr size_t kStaticBytes = kStaticPartialsBytes + kStaticPart2Bytes + kStaticCoefBytes + kStaticStateBytes;
+static_assert(kStaticPartialsBytes % 256 == 0 && kStaticPart2Bytes % 256 == 0 && kStaticCoefBytes % 256 == 0,
+              "every part of the scratch starts on a 256-byte boundary");
+static_assert(sizeof(DevState) <= kStaticStateBytes, "state block");
+
+// In host code this name is only a stand-in for the symbol: the memory is reached through the
+// address that hipGetSymbolAddress returns for the current device (static_ctx below).
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+constexpr int kMaxDevices = 64;
+struct StaticCtx {
+    bool ready = false;
+    svgd_ctx ctx;
+};
+std::mutex g_static_mutex;
+StaticCtx g_static[kMaxDevices];
+
+// The per-device context of svgd_step_static, set up on the first call on that device (which must
+// be the current one).  Returns nullptr and sets *rc on failure.
+svgd_ctx *static_ctx(int dev, int *rc)
+{
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    StaticCtx &sc = g_static[dev];
+    if (sc.ready) return &sc.ctx;
+    unsigned char *ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || ptr == nullptr) {
+        (void)hipGetLastError();
+        *rc = SVGD_ERR_DEVICE;
+        return nullptr;
+    }
+    int cus = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess || cus < 1) {
+        (void)hipGetLastError();
+        *rc = SVGD_ERR_DEVICE;
+        return nullptr;
+    }
+    svgd_ctx &c = sc.ctx;
+    c.magic = kMagic;
+    c.device = dev;
+    c.max_n = SVGD_MAX_PARTICLES;
+    c.max_D = SVGD_STATIC_MAX_D;
+    c.num_cu = cus > 256 ? 256 : cus; // keeps the Gram grid (2 workgroups per CU) within kStaticMaxParts
+    c.flags = 0;
+    c.h_fixed = 0.0;
+    c.carry_valid = false;
+    c.carry_X = nullptr;
+    c.carry_n = 0;
+    c.carry_D = c.carry_ld = 0;
+    c.carry_nparts = 0;
+    c.carry_stream = nullptr;
+    c.last_n = 0;
+    c.last_hip_error = 0;
+    c.partials = reinterpret_cast<float *>(ptr);
+    c.partials_cap = (int64_t)kStaticMaxParts * kMaxPairsFull;
+    c.part2 = reinterpret_cast<double *>(ptr + kStaticPartialsBytes);
+    c.coef = reinterpret_cast<float *>(ptr + kStaticPartialsBytes + kStaticPart2Bytes);
+    c.state = reinterpret_cast<DevState *>(ptr + kStaticPartialsBytes + kStaticPart2Bytes + kStaticCoefBytes);
+    c.profiling = false;
+    c.profile_kinds = 0;
+    sc.ready = true;
+    return &c;
+}
+
 } // namespace
 
 extern "C" {
@@ -487,6 +561,30 @@ int svgd_phi_ld(svgd_handle_t c, const float *X, const float *G, int n, int64_t 
 int svgd_phi(svgd_handle_t c, const float *X, const float *G, int n, int64_t D, float *PHI, void *stream)
 {
     return svgd_phi_ld(c, X, G, n, D, D, PHI, stream);
+}
+
+int svgd_step_static(float *X, const float *G, int n, int64_t D, int64_t ld, float eps, void *stream)
+{
+    if (!X || !G || !std::isfinite(eps) || n < 1 || D < 1 || ld < D) return SVGD_ERR_INVALID_ARG;
+    if (n > SVGD_MAX_PARTICLES || D > SVGD_STATIC_MAX_D) return SVGD_ERR_TOO_LARGE;
+    if (overlaps(X, G, n, D, ld)) return SVGD_ERR_INVALID_ARG;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return SVGD_ERR_DEVICE;
+    }
+    if (dev < 0 || dev >= kMaxDevices) return SVGD_ERR_DEVICE;
+    int rc = SVGD_OK;
+    svgd_ctx *c = static_ctx(dev, &rc);
+    if (!c) return rc;
+    // Every part of the scratch that a kernel reads has been written by an earlier kernel of the
+    // same call (partials by all workgroups of the pairwise-d2 pass, their sums, the state and
+    // the coefficient tables by the passes after it): nothing has to start at zero.
+    hipStream_t s = (hipStream_t)stream;
+    if (is_tiny(n, D)) return run_tiny<kTinyStep>(c, X, G, nullptr, n, D, ld, eps, s);
+    rc = run_kernel_matrix(c, X, n, D, ld, s, false);
+    if (rc) return rc;
+    return run_update<false, false>(c, X, G, nullptr, n, D, ld, eps, s);
 }
 
 int svgd_get_last(svgd_handle_t c, double *h_out, float *K_host, void *stream)

@@ -41,6 +41,9 @@ _lib.svgd_diag_copy.restype = ctypes.c_int
 _lib.svgd_diag_axpy_rows.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                      ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
 _lib.svgd_diag_axpy_rows.restype = ctypes.c_int
+_lib.svgd_step_static.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                  ctypes.c_float, ctypes.c_void_p]
+_lib.svgd_step_static.restype = ctypes.c_int
 _lib.swag_update_moments.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                      ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p]
 _lib.swag_update_moments.restype = ctypes.c_int
@@ -65,6 +68,7 @@ SVGD_OK = 0
 FLAG_CARRY_GRAM = 1
 KERNEL_KINDS = ("gram", "reduce", "bandwidth", "update")
 MAX_PARTICLES = 64
+STATIC_MAX_D = 1 << 32
 
 
 class SvgdError(RuntimeError):
@@ -131,6 +135,19 @@ def diag_axpy_rows(X: torch.Tensor, G: torch.Tensor, s: float, pattern: int, wor
     n, D, ld = shape
     rc = _lib.svgd_diag_axpy_rows(X.data_ptr(), G.data_ptr(), n, D, ld, float(s), int(pattern), int(workgroups),
                                   _stream_ptr(stream))
+    if rc != SVGD_OK:
+        raise SvgdError(rc)
+
+
+def step_static(X: torch.Tensor, G: torch.Tensor, eps: float, stream=None):
+    """svgd_step_static: one plain step on the current device with the library's static scratch -
+    no handle, nothing allocated.  X and G as in Svgd.step."""
+    shape = _rows_of(X, "X")
+    if _rows_of(G, "G") != shape:
+        raise ValueError("G must have the shape and row stride of X")
+    n, D, ld = shape
+    with torch.cuda.device(X.device):
+        rc = _lib.svgd_step_static(X.data_ptr(), G.data_ptr(), n, D, ld, float(eps), _stream_ptr(stream))
     if rc != SVGD_OK:
         raise SvgdError(rc)
 
