@@ -62,6 +62,12 @@ __device__ inline f32x4 load4_stream(const float *__restrict__ row, int64_t col,
     return load4(row, col, D, false);
 }
 
+// rows that all start on a 128-byte boundary
+__host__ inline bool rows_aligned(const void *base, int64_t ld)
+{
+    return (ld & 31) == 0 && (reinterpret_cast<uintptr_t>(base) & 127) == 0;
+}
+
 __device__ inline void store4(float *__restrict__ row, int64_t col, int64_t D, bool full, f32x4 v)
 {
     if (full) {

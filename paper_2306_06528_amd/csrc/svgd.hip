@@ -254,8 +254,9 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int grid = clampi((nfull + 3) / 4, 1, max_workers) + 1;
         const int NB = (n + 15) / 16;
         if (CARRY) c->carry_nparts = grid; // one partial per workgroup, the tail's included
-        // rows that all start on a 128-byte boundary need no re-aligned stores
-        const bool aligned = !EMIT && (ld & 31) == 0 && (reinterpret_cast<uintptr_t>(X) & 127) == 0;
+        // rows that all start on a 128-byte boundary (X's and G's) need no re-aligned stores and
+        // can be read with streaming loads
+        const bool aligned = !EMIT && rows_aligned(X, ld) && rows_aligned(G, ld);
 #define UPD(NBV, FULL)                                                                                       \
     do {                                                                                                     \
         if (!EMIT && aligned)                                                                                \

@@ -280,12 +280,27 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     }
     __syncthreads();
 
-    // this wave's contiguous range of tiles
-    const int64_t nwaves = (int64_t)(gridDim.x - 1) * 4;
-    const int64_t per = (nfull + nwaves - 1) / nwaves;
-    const int64_t w = (int64_t)blockIdx.x * 4 + wave;
-    const int64_t t0 = (w * per < nfull) ? w * per : nfull;
-    const int64_t t1 = (t0 + per < nfull) ? t0 + per : nfull;
+    // The tiles of this wave: t0, t0 + TS, ... < t1.  Re-aligned stores hand a row's tail from one
+    // tile to the next through the wave's carry, so there each wave walks a contiguous range of
+    // its own (TS = 1).  ALIGNED has nothing to hand over: at n > 48 the workgroup owns a
+    // contiguous range and its four waves take adjacent tiles (TS = 4), which makes the
+    // workgroup's accesses 1 KiB contiguous per row (0.5-1 % faster at n = 64; at n = 32, where the
+    // working set is close to the memory-side cache, it measured 3 % slower and is not used).
+    constexpr int64_t TS = (ALIGNED && NB == 4) ? 4 : 1;
+    int64_t t0, t1;
+    if constexpr (TS == 4) {
+        const int64_t nwg = gridDim.x - 1;
+        const int64_t per = (nfull + nwg - 1) / nwg;
+        const int64_t b0 = ((int64_t)blockIdx.x * per < nfull) ? (int64_t)blockIdx.x * per : nfull;
+        t1 = (b0 + per < nfull) ? b0 + per : nfull;
+        t0 = (b0 + wave < t1) ? b0 + wave : t1;
+    } else {
+        const int64_t nwaves = (int64_t)(gridDim.x - 1) * 4;
+        const int64_t per = (nfull + nwaves - 1) / nwaves;
+        const int64_t w = (int64_t)blockIdx.x * 4 + wave;
+        t0 = (w * per < nfull) ? w * per : nfull;
+        t1 = (t0 + per < nfull) ? t0 + per : nfull;
+    }
     const int64_t c_begin = t0 << 6;
 
     // lane part of every load address: row 4q, column 4c; the rest is wave-uniform
@@ -297,33 +312,49 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     const uint32_t a0 = (uint32_t)(reinterpret_cast<uintptr_t>(OUT) >> 2) & 31u;
 
     // Software pipeline across tiles: the loads of tile t+1 are issued while tile t is being
-    // multiplied.  Two schedules, chosen by measurement:
-    //   DBUF (NB <= 2): all of them at the top of tile t into a second set of registers - small
-    //     tiles are short, and the loads need the whole tile time to come back;
-    //   otherwise: into the registers of tile t as they fall free - x rows of block bi after that
-    //     block's epilogue, g rows of step group sg after the last block has consumed them (more
-    //     requests in flight only added HBM contention at n = 64).
+    // multiplied.  Schedules chosen by measurement:
+    //   XBUF (NB <= 2): the x rows of tile t+1 are loaded at the top of tile t into a second set of
+    //     registers - small tiles are short, and the loads need the whole tile time to come back;
+    //     otherwise into the registers of tile t as they fall free, the rows of block bi after
+    //     that block's epilogue (more requests in flight only added HBM contention at n = 64);
+    //   GBUF (NB <= 2, or CARRY): the same for the g rows.  Without it they are fetched as the last
+    //     output block consumes them, i.e. issued last and needed first by the next tile; the
+    //     longer tile of the carried sums then waits for them at every tile start (1.75 -> 1.72 ms
+    //     at n = 64), while the plain update, which waits on memory anyway, is not helped.
     // The last tile of the range "prefetches" itself again (a few KB that nobody uses) so that the
     // steady-state code has no branch.
-    constexpr bool DBUF = (NB <= 2);
-    f32x4 x[NS], z[NS], xn[DBUF ? NS : 1], gn[DBUF ? NS : 1];
+    constexpr bool XBUF = (NB <= 2);
+    constexpr bool GBUF = (NB <= 2) || CARRY;
+    f32x4 x[NS], z[NS], xn[XBUF ? NS : 1], gn[GBUF ? NS : 1];
+    // G is read exactly once per step.  When no cache line is shared between tiles or rows
+    // (ALIGNED) it is loaded with the streaming hint, which does not allocate on the way in:
+    // measurably faster (a plain read-read-write stream over these buffers runs at 5.25 instead of
+    // 5.08 TB/s), and it leaves the memory-side cache to X, which this kernel reads again in the
+    // next step - at n = 32, D = 2,000,000 (X is 256 MB) that alone takes the update from 154 to
+    // 119 us.  X itself is therefore loaded plainly.  With unaligned rows the line that a row
+    // segment shares with the next tile has to stay cached, so nothing streams.
+    auto load16x = [](const float *p) __attribute__((always_inline)) -> f32x4 {
+        return *reinterpret_cast<const f32x4u *>(p);
+    };
+    auto load16g = [](const float *p) __attribute__((always_inline)) -> f32x4 {
+        if constexpr (ALIGNED) return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(p));
+        else return *reinterpret_cast<const f32x4u *>(p);
+    };
     auto load_x = [&](const float *xt, int s) __attribute__((always_inline)) {
         const int urow = 16 * (s >> 2) + (s & 3); // uniform part of the row index
-        if (FULLROWS || urow + 4 * q < n) x[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * ld);
+        if (FULLROWS || urow + 4 * q < n) x[s] = load16x(xt + (int64_t)urow * ld);
     };
     auto load_g = [&](const float *gt, int s) __attribute__((always_inline)) {
         const int urow = 16 * (s >> 2) + (s & 3);
-        if (FULLROWS || urow + 4 * q < n) z[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * ld);
+        if (FULLROWS || urow + 4 * q < n) z[s] = load16g(gt + (int64_t)urow * ld);
     };
     auto load_next = [&](const float *xt, const float *gt) __attribute__((always_inline)) {
-        if constexpr (DBUF) {
 #pragma unroll
-            for (int s = 0; s < NS; ++s) {
-                const int urow = 16 * (s >> 2) + (s & 3);
-                if (FULLROWS || urow + 4 * q < n) {
-                    xn[s] = *reinterpret_cast<const f32x4u *>(xt + (int64_t)urow * ld);
-                    gn[s] = *reinterpret_cast<const f32x4u *>(gt + (int64_t)urow * ld);
-                }
+        for (int s = 0; s < NS; ++s) {
+            const int urow = 16 * (s >> 2) + (s & 3);
+            if (FULLROWS || urow + 4 * q < n) {
+                if constexpr (XBUF) xn[s] = load16x(xt + (int64_t)urow * ld);
+                if constexpr (GBUF) gn[s] = load16g(gt + (int64_t)urow * ld);
             }
         }
     };
@@ -334,13 +365,10 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         for (int s = 0; s < NS; ++s) {
             x[s] = f32x4{0.f, 0.f, 0.f, 0.f};
             z[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if constexpr (DBUF) {
-                xn[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-                gn[s] = f32x4{0.f, 0.f, 0.f, 0.f};
-            } else {
-                load_x(X + in_off, s);
-                load_g(G + in_off, s);
-            }
+            if constexpr (XBUF) xn[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            else load_x(X + in_off, s);
+            if constexpr (GBUF) gn[s] = f32x4{0.f, 0.f, 0.f, 0.f};
+            else load_g(G + in_off, s);
         }
         load_next(X + in_off, G + in_off);
     }
@@ -348,7 +376,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     auto process_tile = [&](auto first_tag, int64_t tile) __attribute__((always_inline)) {
         constexpr bool FIRST = decltype(first_tag)::value;
         const int64_t base = tile << 6;
-        const int64_t next = (tile + 1 < t1) ? tile + 1 : tile;
+        const int64_t next = (tile + TS < t1) ? tile + TS : tile;
         int64_t in_off = in_lane + (next << 6);
         int64_t out_off = out_lane + base;
         const int qv = q; // (the per-row store offsets are tile-invariant and may be hoisted)
@@ -356,11 +384,11 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         const float *xt = X + in_off, *gt = G + in_off;
         float *ot = OUT + out_off;
 
-        if constexpr (DBUF) { // this tile's data becomes current, the next tile's loads go out
+        if constexpr (XBUF || GBUF) { // this tile's data becomes current, the next tile's loads go out
 #pragma unroll
             for (int s = 0; s < NS; ++s) {
-                x[s] = xn[s];
-                z[s] = gn[s];
+                if constexpr (XBUF) x[s] = xn[s];
+                if constexpr (GBUF) z[s] = gn[s];
             }
             load_next(xt, gt);
         }
@@ -444,7 +472,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
                         acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[k], z[4 * sg + k][t], acc[t], 0, 0, 0);
-                if (!DBUF && bi == NB - 1) { // z rows 4sg..4sg+3 are dead: fetch the next tile's g
+                if (!GBUF && bi == NB - 1) { // z rows 4sg..4sg+3 are dead: fetch the next tile's g
 #pragma unroll
                     for (int k = 0; k < 4; ++k) load_g(gt, 4 * sg + k);
                 }
@@ -476,7 +504,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 if constexpr (!ALIGNED || CARRY) // staged for the re-aligned stores and/or as Gram operands
                     *reinterpret_cast<f32x4 *>(&cur[cur_index(4 * q + r, 4 * c16)]) = o;
             }
-            if constexpr (!DBUF) { // x rows of this block are dead: fetch the next tile's
+            if constexpr (!XBUF) { // x rows of this block are dead: fetch the next tile's
 #pragma unroll
                 for (int r = 0; r < 4; ++r) load_x(xt, 4 * bi + r);
             }
@@ -501,7 +529,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     };
 
     if constexpr (ALIGNED) { // no left edge to mask
-        for (int64_t tile = t0; tile < t1; ++tile) process_tile(std::false_type{}, tile);
+        for (int64_t tile = t0; tile < t1; tile += TS) process_tile(std::false_type{}, tile);
     } else if (t0 < t1) {
         process_tile(std::true_type{}, t0);
         for (int64_t tile = t0 + 1; tile < t1; ++tile) process_tile(std::false_type{}, tile);
