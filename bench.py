@@ -231,13 +231,13 @@ def main():
 
     def triad_ceiling(Xv, Gv):
         """What the memory system gives the update's traffic and nothing else: x += s*g in place
-        over the same row streams of the same buffers (s = 0: X keeps its values), best of the two
-        access patterns and a few grid sizes.  GB/s at 12 bytes per element."""
+        over the same row streams of the same buffers (s = 0: X keeps its values), best of the
+        access patterns (two shapes, two depths, with and without streaming loads) and grid sizes.  GB/s at 12 bytes per element."""
         cus = torch.cuda.get_device_properties(0).multi_processor_count
         best = None
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         reps = 10
-        for pattern in (0, 1, 2, 3):
+        for pattern in range(8):
             for per_cu in (1, 2, 4, 8):
                 for _ in range(3):
                     svgd.diag_axpy_rows(Xv, Gv, 0.0, pattern, cus * per_cu, stream=stream)

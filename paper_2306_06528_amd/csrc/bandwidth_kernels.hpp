@@ -21,6 +21,258 @@ struct BwShared {
     double h;
 };
 
+// A double moved across lanes by a DPP control word (both halves).
+template <int CTRL>
+__device__ inline double dpp_f64(double v)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    lo = __builtin_amdgcn_update_dpp(0, lo, CTRL, 0xF, 0xF, false);
+    hi = __builtin_amdgcn_update_dpp(0, hi, CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+
+__device__ inline double readlane_f64(double v, int lane)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+
+// Minimum and maximum over the 64 lanes of a wave, returned in every lane (four DPP steps inside
+// each row of 16 lanes, then the four rows; no LDS traffic).
+__device__ inline void wave_minmax(double &mn, double &mx)
+{
+#define SVGD_MM_STEP(C)                                                                            \
+    mn = fmin(mn, dpp_f64<C>(mn));                                                                 \
+    mx = fmax(mx, dpp_f64<C>(mx));
+    SVGD_MM_STEP(0xB1)  // quad_perm [1,0,3,2]
+    SVGD_MM_STEP(0x4E)  // quad_perm [2,3,0,1]
+    SVGD_MM_STEP(0x141) // row_half_mirror
+    SVGD_MM_STEP(0x140) // row_mirror
+#undef SVGD_MM_STEP
+    mn = fmin(fmin(readlane_f64(mn, 0), readlane_f64(mn, 16)), fmin(readlane_f64(mn, 32), readlane_f64(mn, 48)));
+    mx = fmax(fmax(readlane_f64(mx, 0), readlane_f64(mx, 16)), fmax(readlane_f64(mx, 32), readlane_f64(mx, 48)));
+}
+
+// Sum over the 64 lanes of a wave, returned in every lane (same steps as wave_minmax).
+__device__ inline double wave_sum_f64(double v)
+{
+    v += dpp_f64<0xB1>(v);
+    v += dpp_f64<0x4E>(v);
+    v += dpp_f64<0x141>(v);
+    v += dpp_f64<0x140>(v);
+    return (readlane_f64(v, 0) + readlane_f64(v, 16)) + (readlane_f64(v, 32) + readlane_f64(v, 48));
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave: four DPP shift-adds inside each row of 16
+// lanes, then the totals of the lower rows (read from lanes 15, 31, 47) are added to the upper ones.
+__device__ inline unsigned wave_inclusive_scan(unsigned x)
+{
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xF, 0xF, true); // row_shr:1, 0 shifted in
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xF, 0xF, true); // row_shr:2
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xF, 0xF, true); // row_shr:4
+    x += (unsigned)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xF, 0xF, true); // row_shr:8
+    const unsigned t0 = (unsigned)__builtin_amdgcn_readlane((int)x, 15);
+    const unsigned t1 = (unsigned)__builtin_amdgcn_readlane((int)x, 31);
+    const unsigned t2 = (unsigned)__builtin_amdgcn_readlane((int)x, 47);
+    const int row = (threadIdx.x & 63) >> 4;
+    return x + (row >= 1 ? t0 : 0u) + (row >= 2 ? t1 : 0u) + (row >= 3 ? t2 : 0u);
+}
+
+// Non-negative doubles (and +inf) order like their bit patterns read as unsigned integers.
+__device__ inline unsigned long long f64_key(double v) { return (unsigned long long)__double_as_longlong(v); }
+__device__ inline double key_f64(unsigned long long k) { return __longlong_as_double((long long)k); }
+
+// The pair values of rank r_lo and r_hi (0-based, r_hi = r_lo or r_lo + 1) among sh.pr[0 .. Pp),
+// written to sh.sel[0] and sh.sel[1].  Exact selection without sorting:
+//   - a small set (<= kSelDirect values) is ranked directly: every element counts how many others
+//     precede it (ties by position), and the elements of the wanted ranks announce themselves;
+//   - a larger one is spread over THREADS buckets by value, bucket(v) = floor((v - a) * THREADS /
+//     (b - a)) clamped, [a, b] = minimum and maximum of the set - monotone in v, so all of bucket
+//     k lies below all of bucket k + 1; the bucket counts are prefix-summed, and the bucket that
+//     holds the wanted ranks becomes the active set (gathered into a list once it is small).
+//     a and b fall into the first and the last bucket, so the set shrinks at every level.  Ranks
+//     that fall into two different buckets are the maximum of the one and the minimum of the other.
+// With n = 64 (2016 values) this takes one level and a short list; the bitonic sort it replaces
+// cost 66 exchange stages.  Everything that crosses waves goes through LDS atomics and a barrier;
+// inside a wave only DPP moves are used (cross-lane reads through LDS cost as much as a barrier).
+// Called by all THREADS threads with Pp <= 2 * THREADS, after a barrier that made sh.pr visible;
+// sh.S is used as scratch.  Values that are not finite or negative cannot be ranked consistently:
+// the loop is bounded and then returns the minimum.
+constexpr int kSelDirect = 128;
+
+// Rank (position in sorted order, ties by index) of every element of a short list; the elements of
+// the wanted ranks are stored.  THREADS / kSelDirect threads share one element, each comparing it
+// with a slice of the list (a single thread walking the whole list would wait for one LDS round
+// trip after the other); the partial ranks meet in LDS counters.  Two barriers inside.
+template <int THREADS>
+__device__ inline void rank_directly(const double *list, int len, int below, int r_lo, int r_hi, double *sel,
+                                     unsigned *counters /* kSelDirect, scratch */)
+{
+    constexpr int PARTS = THREADS / kSelDirect;           // threads per element
+    constexpr int SLICE = (kSelDirect + PARTS - 1) / PARTS; // list entries per thread
+    static_assert(PARTS >= 1 && PARTS * kSelDirect == THREADS, "THREADS is a multiple of kSelDirect");
+    const int tid = threadIdx.x;
+    const int e = tid % kSelDirect, part = tid / kSelDirect;
+    if (part == 0) counters[e] = 0;
+    __syncthreads();
+    double v = 0.0;
+    if (e < len) {
+        v = list[e];
+        unsigned cnt = 0;
+        const int u0 = part * SLICE;
+#pragma unroll
+        for (int k = 0; k < SLICE; ++k) {
+            const int u = u0 + k;
+            if (u < len) {
+                const double w = list[u];
+                cnt += (w < v || (w == v && u < e)) ? 1u : 0u;
+            }
+        }
+        if (cnt) atomicAdd(&counters[e], cnt);
+    }
+    __syncthreads();
+    if (part == 0 && e < len) {
+        const int rank = below + (int)counters[e];
+        if (rank == r_lo) sel[0] = v;
+        if (rank == r_hi) sel[1] = v;
+    }
+}
+
+template <int THREADS>
+__device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi)
+{
+    static_assert(THREADS % 64 == 0 && THREADS >= 256 && THREADS <= 1024, "one bucket per thread, at most 16 waves");
+    constexpr int NW = THREADS / 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    if (Pp <= kSelDirect) { // the whole set is small: no buckets, no gathering
+        rank_directly<THREADS>(sh.pr, Pp, 0, r_lo, r_hi, sh.sel, reinterpret_cast<unsigned *>(sh.S));
+        return; // the caller's barrier publishes sel
+    }
+    // scratch inside S (free by now): [hist: THREADS u32][misc: 16 u32][wave totals: 16 u32][min/max keys: 4 u64][list: kSelDirect f64]
+    unsigned *hist = reinterpret_cast<unsigned *>(sh.S);
+    unsigned *misc = hist + THREADS; // 0: list length, 1: bucket of r_lo, 2: bucket of r_hi, 3: values below the bucket of r_lo, 4: its count
+    unsigned *wsum = misc + 16;
+    unsigned long long *mm = reinterpret_cast<unsigned long long *>(wsum + 16); // 0: min, 1: max, 2: min (second use), 3: max
+    double *list = reinterpret_cast<double *>(mm + 4);
+    static_assert((THREADS + 32) % 2 == 0 && (THREADS + 32) / 2 + 4 + kSelDirect <= kMaxPairsFull, "scratch fits in S, 8-byte aligned");
+    const unsigned long long kmax = ~0ull;
+
+    // every thread owns up to two values
+    const double e0 = (tid < Pp) ? sh.pr[tid] : 0.0;
+    const double e1 = (tid + THREADS < Pp) ? sh.pr[tid + THREADS] : 0.0;
+    bool act0 = tid < Pp, act1 = tid + THREADS < Pp;
+    int below = 0; // values known to be smaller than the whole active set
+    int cnt = Pp;  // size of the active set
+    const double inf = __builtin_huge_val();
+
+    // minimum and maximum of the calling threads' values: DPP inside the wave, one LDS atomic per
+    // wave on the bit patterns, one barrier.  slot: 0 or 2 (alternating, so that a slot can be
+    // re-initialised behind the barrier of the other one's use)
+    auto block_minmax = [&](double mn, double mx, int slot, double &a, double &b) {
+        wave_minmax(mn, mx);
+        if (lane == 0) {
+            atomicMin(&mm[slot], f64_key(mn));
+            atomicMax(&mm[slot + 1], f64_key(fmax(mx, 0.0)));
+        }
+        __syncthreads();
+        a = key_f64(mm[slot]);
+        b = key_f64(mm[slot + 1]);
+    };
+
+    for (int level = 0; level < 12; ++level) {
+        const int slot = (level & 1) * 2;
+        hist[tid] = 0;
+        if (tid < 16) misc[tid] = (tid == 0) ? 0u : 0xFFFFFFFFu;
+        if (tid == 0) { // the other slot, for the next use
+            mm[2 - slot] = kmax;
+            mm[3 - slot] = 0ull;
+        }
+        if (level == 0) { // (later levels find their slot prepared by the level before)
+            if (tid == 0) {
+                mm[0] = kmax;
+                mm[1] = 0ull;
+            }
+            __syncthreads();
+        }
+        double a, b;
+        block_minmax(fmin(act0 ? e0 : inf, act1 ? e1 : inf), fmax(act0 ? e0 : 0.0, act1 ? e1 : 0.0), slot, a, b);
+        if (!(a < b)) { // all active values equal (or nothing rankable): both ranks are a
+            if (tid == 0) {
+                sh.sel[0] = a;
+                sh.sel[1] = a;
+            }
+            return;
+        }
+        // spread the active values over THREADS buckets
+        const double scale = (double)THREADS / (b - a);
+        auto bucket = [&](double v) {
+            const int k = (int)((v - a) * scale);
+            return k < 0 ? 0 : (k > THREADS - 1 ? THREADS - 1 : k);
+        };
+        const int k0 = act0 ? bucket(e0) : 0, k1 = act1 ? bucket(e1) : 0;
+        if (act0) atomicAdd(&hist[k0], 1u);
+        if (act1) atomicAdd(&hist[k1], 1u);
+        __syncthreads();
+        // inclusive prefix sum of the bucket counts: DPP inside the wave, wave totals through LDS
+        const unsigned mine = hist[tid];
+        unsigned incl = wave_inclusive_scan(mine);
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        unsigned before = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) before += (w < wave) ? wsum[w] : 0u;
+        incl += before;
+        const unsigned excl = incl - mine;
+        // the buckets holding the wanted ranks (ranks relative to the active set)
+        const unsigned q_lo = (unsigned)(r_lo - below), q_hi = (unsigned)(r_hi - below);
+        if (mine > 0 && excl <= q_lo && q_lo < incl) {
+            misc[1] = (unsigned)tid;
+            misc[3] = excl;
+            misc[4] = mine;
+        }
+        if (mine > 0 && excl <= q_hi && q_hi < incl) misc[2] = (unsigned)tid;
+        __syncthreads();
+        const unsigned b_lo = misc[1], b_hi = misc[2];
+        if (b_lo == 0xFFFFFFFFu || b_hi == 0xFFFFFFFFu) { // unrankable input: give up with a
+            if (tid == 0) {
+                sh.sel[0] = a;
+                sh.sel[1] = a;
+            }
+            return;
+        }
+        if (b_lo != b_hi) {
+            // adjacent ranks in different buckets: the largest value of the one, the smallest of the other
+            double mx = 0.0, mn = inf;
+            if (act0 && (unsigned)k0 == b_lo) mx = fmax(mx, e0);
+            if (act1 && (unsigned)k1 == b_lo) mx = fmax(mx, e1);
+            if (act0 && (unsigned)k0 == b_hi) mn = fmin(mn, e0);
+            if (act1 && (unsigned)k1 == b_hi) mn = fmin(mn, e1);
+            double lo_v, hi_v;
+            block_minmax(mn, mx, 2 - slot, hi_v, lo_v);
+            if (tid == 0) {
+                sh.sel[0] = lo_v;
+                sh.sel[1] = hi_v;
+            }
+            return;
+        }
+        below += (int)misc[3];
+        cnt = (int)misc[4];
+        act0 = act0 && (unsigned)k0 == b_lo;
+        act1 = act1 && (unsigned)k1 == b_lo;
+        if (cnt <= kSelDirect) { // gather the bucket into a list and rank it
+            if (act0) list[atomicAdd(&misc[0], 1u)] = e0;
+            if (act1) list[atomicAdd(&misc[0], 1u)] = e1;
+            rank_directly<THREADS>(list, cnt, below, r_lo, r_hi, sh.sel, hist);
+            return;
+        }
+        __syncthreads(); // all reads of misc, hist and wsum are done before the next level clears them
+    }
+    if (tid == 0) {
+        sh.sel[0] = sh.pr[0];
+        sh.sel[1] = sh.pr[0];
+    }
+}
+
 // From the reduced pair sums in sh.S[0 .. n(n+1)/2) to h, K and the coefficient tables.  Called by
 // all THREADS threads of a workgroup (2 * THREADS >= n(n-1)/2 rounded up to a power of two), which
 // have written sh.S before (no barrier needed in between).  coef_lds, if not null, receives C [n*n] and rho [n] as well (LDS of the caller);
@@ -30,87 +282,45 @@ __device__ inline void bandwidth_from_sums(BwShared &sh, int n, int mode, double
                                            DevState *__restrict__ st, float *__restrict__ coef,
                                            float *coef_lds)
 {
-    static_assert(THREADS % 64 == 0 && 2 * THREADS <= kMaxPairsFull, "the sort exchanges 2 * THREADS values through S");
+    static_assert(THREADS % 64 == 0, "whole waves");
     const int tid = threadIdx.x;
     const int Pp = n * (n - 1) / 2;
     if (tid < 2) sh.sel[tid] = 0.0;
     __syncthreads();
 
-    // d2 per pair: direct sums, or S_ii + S_jj - 2 S_ij (clamped at 0) from the centred Gram
-    for (int i = tid >> 6; i < n; i += THREADS / 64) {   // wave -> row, lane -> column
-        for (int j = i + 1 + (tid & 63); j < n; j += 64) {
-            double d;
-            if (mode == kModeDiff) {
-                d = sh.S[tri(i, j, n)];
-            } else {
-                d = sh.S[tri(i, i, n)] + sh.S[tri(j, j, n)] - 2.0 * sh.S[tri(i, j, n)];
-            }
-            if (!(d > 0.0)) d = 0.0; // clamps rounding negatives (and -0.0)
-            sh.pr[pair_index(i, j, n)] = d;
+    // d2 per pair: direct sums, or S_ii + S_jj - 2 S_ij (clamped at 0) from the centred Gram.
+    // Thread p takes pair p: row i is the largest one whose first pair index, i (2n - i - 1) / 2,
+    // does not exceed p (estimate from the quadratic, then corrected).
+    for (int p = tid; p < Pp; p += THREADS) {
+        const float tn = (float)(2 * n - 1);
+        int i = (int)(0.5f * (tn - sqrtf(fmaxf(tn * tn - 8.0f * (float)p, 0.0f))));
+        i = i < 0 ? 0 : (i > n - 2 ? n - 2 : i);
+        while (i > 0 && pair_index(i, i + 1, n) > p) --i;
+        while (i < n - 2 && pair_index(i + 1, i + 2, n) <= p) ++i;
+        const int j = i + 1 + (p - pair_index(i, i + 1, n));
+        double d;
+        if (mode == kModeDiff) {
+            d = sh.S[tri(i, j, n)];
+        } else {
+            d = sh.S[tri(i, i, n)] + sh.S[tri(j, j, n)] - 2.0 * sh.S[tri(i, j, n)];
         }
+        if (!(d > 0.0)) d = 0.0; // clamps rounding negatives (and -0.0, and NaN)
+        sh.pr[p] = d;
     }
     __syncthreads();
 
     // Median of the multiset of all n*n entries of d2: n diagonal zeros plus every pair value
     // twice.  Sorted position t of the full list is 0 for t < n and the ((t-n)/2)-th smallest
-    // pair value otherwise; an even count averages positions n*n/2 - 1 and n*n/2.  S is free by
-    // now and serves as the exchange buffer of the sort.
+    // pair value otherwise; an even count averages positions n*n/2 - 1 and n*n/2.  So what is
+    // needed are the pair values of rank r_lo and r_hi (equal or adjacent), not a sorted list.
+    const int t_lo = (n * n - 1) / 2, t_hi = (n * n) / 2; // t_hi >= n for every n >= 2
     if (h_fixed <= 0.0 && Pp > 0) {
-        // Bitonic sort of the pair values, two per thread in registers (padded with +inf to a
-        // power of two M <= 2 * THREADS).  Thread t owns elements 2t and 2t+1; a stage at
-        // distance j pairs element i with i^j: inside the thread for j = 1, in lane t ^ (j/2) of
-        // the same wave for j <= 64 (shuffles), through LDS for wider stages (10 of the 66
-        // stages at M = 2048).  (Eight values per thread with every stage inside a thread and
-        // LDS re-deals in between was measured slower: too few waves to hide the latencies.)
-        int M = 2;
-        while (M < Pp) M <<= 1;
-        double e0 = (2 * tid < Pp) ? sh.pr[2 * tid] : __builtin_huge_val();
-        double e1 = (2 * tid + 1 < Pp) ? sh.pr[2 * tid + 1] : __builtin_huge_val();
-        // waves that hold nothing but padding sit the stages out (they still meet the barriers)
-        const bool act = 2 * (tid & ~63) < M;
-        for (int k = 2; k <= M; k <<= 1) {
-            const bool up = (((2 * tid) & k) == 0); // same for both elements (k >= 2)
-            for (int j = k >> 1; j > 0; j >>= 1) {
-                const int half = j >> 1;
-                double p0 = e1, p1 = e0; // j == 1: the partner is the thread's other element
-                if (half >= 64) {
-                    if (act) {
-                        sh.S[2 * tid] = e0;
-                        sh.S[2 * tid + 1] = e1;
-                    }
-                    __syncthreads();
-                    if (act) {
-                        const int tp = tid ^ half;
-                        p0 = sh.S[2 * tp];
-                        p1 = sh.S[2 * tp + 1];
-                    }
-                    __syncthreads();
-                } else if (act && half > 0) {
-                    p0 = __shfl_xor(e0, half, kWave);
-                    p1 = __shfl_xor(e1, half, kWave);
-                }
-                if (act) {
-                    // the lower element of an ascending pair keeps the minimum
-                    const bool low0 = (j == 1) ? true : ((tid & half) == 0);
-                    const bool low1 = (j == 1) ? false : low0;
-                    e0 = (low0 == up) ? fmin(e0, p0) : fmax(e0, p0);
-                    e1 = (low1 == up) ? fmin(e1, p1) : fmax(e1, p1);
-                }
-            }
-        }
-        sh.S[2 * tid] = e0;
-        sh.S[2 * tid + 1] = e1;
-        __syncthreads();
-        if (tid == 0) {
-            const int n2 = n * n;
-            const int t_lo = (n2 - 1) / 2, t_hi = n2 / 2;
-            sh.sel[0] = (t_lo >= n) ? sh.S[(t_lo - n) / 2] : 0.0;
-            sh.sel[1] = (t_hi >= n) ? sh.S[(t_hi - n) / 2] : 0.0;
-        }
+        // n = 2: position t_lo is one of the diagonal zeros - the other rank is selected twice
+        select_two_ranks<THREADS>(sh, Pp, (t_lo >= n) ? (t_lo - n) / 2 : (t_hi - n) / 2, (t_hi - n) / 2);
     }
     __syncthreads();
     if (tid == 0) {
-        double med = 0.5 * (sh.sel[0] + sh.sel[1]);
+        double med = 0.5 * ((t_lo >= n ? sh.sel[0] : 0.0) + sh.sel[1]);
         double h = (h_fixed > 0.0) ? h_fixed : med / log((double)n + 1.0);
         if (!(h > 0.0)) h = 1.0;
         sh.h = h;
@@ -136,29 +346,11 @@ __device__ inline void bandwidth_from_sums(BwShared &sh, int n, int mode, double
             coef[kOffC + i * n + j] = (float)(k * inv_n);
             if (coef_lds) coef_lds[i * n + j] = (float)(k * inv_n);
         }
-#pragma unroll
-        for (int d = 32; d > 0; d >>= 1) r += __shfl_xor(r, d, kWave); // row sum of K
+        r = wave_sum_f64(r); // row sum of K
         if ((tid & 63) == 0) {
             const float rho = (float)(c2h * r * inv_n);
             coef[kOffRho + i] = rho;
             if (coef_lds) coef_lds[n * n + i] = rho;
-        }
-    }
-    // A operands of v_mfma_f32_16x16x4_f32 for the matrix-core update kernel: for output block
-    // bi and step s = 4b + r, lane (q = lane/16, m = lane%16) holds C[16bi + m][16b + 4q + r].
-    if (n > kValuMaxN) {
-        const int NB = (n + 15) / 16;
-        const int total = NB * 4 * NB * kWave;
-        for (int e = tid; e < total; e += THREADS) {
-            const int lane = e & 63;
-            const int s = (e >> 6) % (4 * NB);
-            const int bi = (e >> 6) / (4 * NB);
-            const int i = 16 * bi + (lane & 15);
-            const int j = 16 * (s >> 2) + 4 * (lane >> 4) + (s & 3);
-            double c = 0.0;
-            if (i < n && j < n)
-                c = ((i == j) ? 1.0 : sh.S[i < j ? pair_index(i, j, n) : pair_index(j, i, n)]) * inv_n;
-            coef[kOffAT + e] = (float)c;
         }
     }
 }

@@ -37,12 +37,10 @@ struct DevState {
 //   C   [n*n]   C_ij = K_ij / n
 //   RHO [n]     rho_i = (2/h) * (sum_j K_ij) / n
 //   K   [n*n]   K_ij (kept for svgd_get_last)
-//   AT  [..]    C re-ordered into per-lane MFMA A operands for the matrix-core update kernel
 constexpr int kOffC = 0;
 constexpr int kOffRho = kOffC + kMaxN * kMaxN;
 constexpr int kOffK = kOffRho + kMaxN;
-constexpr int kOffAT = kOffK + kMaxN * kMaxN;
-constexpr int kCoefFloats = kOffAT + (kMaxN / 16) * (kMaxN / 4) * kWave;
+constexpr int kCoefFloats = kOffK + kMaxN * kMaxN;
 
 __device__ inline f32x4 load4(const float *__restrict__ row, int64_t col, int64_t D, bool full)
 {

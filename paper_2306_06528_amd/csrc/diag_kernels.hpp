@@ -25,8 +25,9 @@ __global__ __launch_bounds__(256) void diag_copy_kernel(const f32x4 *__restrict_
 // and masked for the stores, so the steady state has no divergent branch.  The waves of a
 // workgroup take adjacent tiles; workgroups stride over the full tiles; the columns after the
 // last full tile are done element-wise by the last workgroup.  Stores carry the streaming hint,
-// as the update's do.
-template <int PAT, int U>
+// as the update's do; NT: so do the loads (only sensible when no cache line is shared between
+// rows, i.e. rows that start on 128-byte boundaries).
+template <int PAT, int U, bool NT>
 __global__ __launch_bounds__(256) void diag_axpy_rows_kernel(float *__restrict__ X, const float *__restrict__ G,
                                                              int n, int64_t D, int64_t ld, float s)
 {
@@ -45,8 +46,13 @@ __global__ __launch_bounds__(256) void diag_axpy_rows_kernel(float *__restrict__
             for (int u = 0; u < U; ++u) {
                 const int row = r0 + u * RPI + lrow;
                 const int64_t off = (int64_t)(row < n ? row : n - 1) * ld + col;
-                x[u] = *reinterpret_cast<const f32x4u *>(X + off);
-                g[u] = *reinterpret_cast<const f32x4u *>(G + off);
+                if constexpr (NT) {
+                    x[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(X + off));
+                    g[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(G + off));
+                } else {
+                    x[u] = *reinterpret_cast<const f32x4u *>(X + off);
+                    g[u] = *reinterpret_cast<const f32x4u *>(G + off);
+                }
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {

@@ -616,15 +616,19 @@ int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream)
 int svgd_diag_axpy_rows(float *X, const float *G, int n, int64_t D, int64_t ld, float s, int pattern,
                         int workgroups, void *stream)
 {
-    if (!X || !G || n < 1 || D < 1 || ld < D || workgroups < 1 || workgroups > 65536 || pattern < 0 || pattern > 3)
+    if (!X || !G || n < 1 || D < 1 || ld < D || workgroups < 1 || workgroups > 65536 || pattern < 0 || pattern > 7)
         return SVGD_ERR_INVALID_ARG;
     if (overlaps(X, G, n, D, ld)) return SVGD_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
     switch (pattern) {
-    case 0: diag_axpy_rows_kernel<0, 8><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    case 1: diag_axpy_rows_kernel<1, 8><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    case 2: diag_axpy_rows_kernel<0, 16><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    default: diag_axpy_rows_kernel<1, 16><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    case 0: diag_axpy_rows_kernel<0, 8, false><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    case 1: diag_axpy_rows_kernel<1, 8, false><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    case 2: diag_axpy_rows_kernel<0, 16, false><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    case 3: diag_axpy_rows_kernel<1, 16, false><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    case 4: diag_axpy_rows_kernel<0, 8, true><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    case 5: diag_axpy_rows_kernel<1, 8, true><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    case 6: diag_axpy_rows_kernel<0, 16, true><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+    default: diag_axpy_rows_kernel<1, 16, true><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
     }
     return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
 }

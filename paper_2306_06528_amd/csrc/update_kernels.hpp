@@ -124,8 +124,8 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 // 16b + 4q + r; the 4 components of the 16-byte load are 4 independent N-tiles (tile t = columns
 // {4c + t}).  The 16x16 result of output block bi puts row 16bi + 4q + r, column c in register r
 // of lane (q, c) - exactly the rows this lane loaded, so x_old is already in place for the
-// epilogue and nothing crosses lanes.  The A operands (C re-ordered by the bandwidth kernel) sit
-// in LDS, shared by the workgroup's 4 waves, and are re-read per output block.
+// epilogue and nothing crosses lanes.  The A operands (C re-ordered into the per-lane layout by
+// the prologue) sit in LDS, shared by the workgroup's 4 waves, and are re-read per output block.
 //
 // Stores.  A row starts at i*ld floats, so in general the rows are not 128-byte aligned and a
 // store of "the tile's columns" would cut cache lines in two for almost every row; partial-line
@@ -264,12 +264,15 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     f32x4 *As4 = reinterpret_cast<f32x4 *>(lds);
     float *cur = lds + NB * NB * 64 * 4 + wave * (kUpdCur + kUpdCarry);
     float *carry = cur + kUpdCur;
-    // A operands for output block bi, steps 4sg..4sg+3, as one float4 per lane
+    // A operands of v_mfma_f32_16x16x4_f32 for output block bi, steps 4sg..4sg+3, as one float4
+    // per lane: for step s = 4sg + k lane (q = l/16, m = l%16) holds C[16bi + m][16sg + 4q + k]
+    // (zero beyond n: rows and columns of the padding take no part)
     for (int e = threadIdx.x; e < NB * NB * 64; e += 256) {
         const int l = e & 63, sg = (e >> 6) % NB, bi = (e >> 6) / NB;
+        const int i = 16 * bi + (l & 15), j0 = 16 * sg + 4 * (l >> 4);
         f32x4 v;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = coef[kOffAT + (bi * NS + 4 * sg + k) * kWave + l];
+        for (int k = 0; k < 4; ++k) v[k] = (i < n && j0 + k < n) ? coef[kOffC + i * n + j0 + k] : 0.f;
         As4[e] = v;
     }
     float rho[NS];

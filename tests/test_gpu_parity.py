@@ -154,6 +154,35 @@ def test_coincident_particles(svgd):
         assert err <= TOL_PHI
 
 
+@pytest.mark.parametrize("n,groups", [(64, 2), (64, 3), (64, 8), (33, 4), (16, 2), (12, 3), (8, 2), (4, 2)])
+def test_clustered_particles_heavy_ties(svgd, n, groups):
+    """Groups of identical particles: d2 takes few distinct values, each many times over (and many
+    exact zeros), so the two middle order statistics sit inside, or right at the edge of, long runs
+    of ties - the median selection has to count them exactly."""
+    D = 3001
+    centres = torch.randn(groups, D, device="cuda")
+    idx = torch.arange(n, device="cuda") % groups
+    X = centres[idx].contiguous()
+    G = torch.randn(n, D, device="cuda")
+    check_one_step(svgd, X, G, 0.01)
+
+
+@pytest.mark.parametrize("n", [64, 40, 32, 20])
+@pytest.mark.parametrize("c", [5.0, 40.0])
+def test_outlier_particles_nested_scales(svgd, n, c):
+    """A few particles far away from the rest, at two scales: nearly all pairwise distances crowd
+    into a sliver of the value range, so the selection has to refine its buckets more than once.
+    (Each outlier is displaced along one coordinate of its own by a multiple of n, which shifts
+    that column's mean by c or 3c only and keeps the fp32 centred Gram of the other particles
+    well conditioned: this is a test of the selection, not of d2.)"""
+    D = 2051
+    X, G = _random_problem(n, D, 3 * n, x_std=1.0)
+    X[0, 0] += c * n
+    X[1, 1] += 3 * c * n
+    X[2, 2] -= c * n
+    check_one_step(svgd, X.contiguous(), G, 0.01)
+
+
 def test_single_particle_is_gradient_ascent(svgd):
     X, G = _random_problem(1, 1000, 3)
     X0 = X.clone()
