@@ -14,11 +14,20 @@ constexpr int kSlices = 8; // slices of the partial reduction (see reduce_partia
 __device__ inline int pair_index(int i, int j, int n) { return i * n - (i * (i + 1)) / 2 + (j - i - 1); } // i < j
 
 // LDS of the bandwidth computation.
+constexpr int kSelDirect = 128; // a set of at most this many values is ranked directly
+
 struct BwShared {
-    double S[kMaxPairsFull];            // reduced sums, sort exchange, K per pair
+    double S[kMaxPairsFull];            // reduced pair sums, later K per pair
     double pr[kMaxN * (kMaxN - 1) / 2]; // d2 per unordered pair i < j (free for other use before)
     double sel[2];
     double h;
+    // scratch of the median selection (select_two_ranks)
+    unsigned long long mm[4];           // min / max bit patterns, two alternating slots
+    double list[kSelDirect];            // the final short list
+    unsigned hist[1024];                // bucket counts, one bucket per thread
+    unsigned counters[kSelDirect];      // partial ranks of the list elements
+    unsigned misc[16];                  // 0: list length, 1: bucket of r_lo, 2: bucket of r_hi, 3: values below it, 4: its count
+    unsigned wsum[16];                  // wave totals of the bucket counts
 };
 
 // A double moved across lanes by a DPP control word (both halves).
@@ -78,10 +87,6 @@ __device__ inline unsigned wave_inclusive_scan(unsigned x)
     return x + (row >= 1 ? t0 : 0u) + (row >= 2 ? t1 : 0u) + (row >= 3 ? t2 : 0u);
 }
 
-// Non-negative doubles (and +inf) order like their bit patterns read as unsigned integers.
-__device__ inline unsigned long long f64_key(double v) { return (unsigned long long)__double_as_longlong(v); }
-__device__ inline double key_f64(unsigned long long k) { return __longlong_as_double((long long)k); }
-
 // The pair values of rank r_lo and r_hi (0-based, r_hi = r_lo or r_lo + 1) among sh.pr[0 .. Pp),
 // written to sh.sel[0] and sh.sel[1].  Exact selection without sorting:
 //   - a small set (<= kSelDirect values) is ranked directly: every element counts how many others
@@ -93,28 +98,48 @@ __device__ inline double key_f64(unsigned long long k) { return __longlong_as_do
 //     a and b fall into the first and the last bucket, so the set shrinks at every level.  Ranks
 //     that fall into two different buckets are the maximum of the one and the minimum of the other.
 // With n = 64 (2016 values) this takes one level and a short list; the bitonic sort it replaces
-// cost 66 exchange stages.  Everything that crosses waves goes through LDS atomics and a barrier;
-// inside a wave only DPP moves are used (cross-lane reads through LDS cost as much as a barrier).
-// Called by all THREADS threads with Pp <= 2 * THREADS, after a barrier that made sh.pr visible;
-// sh.S is used as scratch.  Values that are not finite or negative cannot be ranked consistently:
-// the loop is bounded and then returns the minimum.
-constexpr int kSelDirect = 128;
+// cost 66 exchange stages.  Everything that crosses waves goes through LDS atomics and a barrier
+// (four barriers on the usual path); inside a wave only DPP moves are used - cross-lane reads
+// through LDS cost as much as a barrier here.
+// Contract: called by all THREADS threads with kSelDirect < Pp <= 2 * THREADS (smaller sets go to
+// rank_directly), after a barrier behind which
+//   - sh.pr holds the values (thread t wrote pr[t] and pr[t + THREADS]),
+//   - sh.mm[0] / mm[1] hold the bit patterns of their minimum / maximum, mm[2] = ~0, mm[3] = 0,
+//   - sh.hist and sh.counters are zero, sh.misc[0] = 0, sh.misc[1..] = ~0
+// (bandwidth_from_sums prepares all of this on its way).  Values that are negative or not finite
+// cannot be ranked consistently: the loop is bounded and then returns some value of the set.
 
-// Rank (position in sorted order, ties by index) of every element of a short list; the elements of
-// the wanted ranks are stored.  THREADS / kSelDirect threads share one element, each comparing it
-// with a slice of the list (a single thread walking the whole list would wait for one LDS round
-// trip after the other); the partial ranks meet in LDS counters.  Two barriers inside.
+// Non-negative doubles (and +inf) order like their bit patterns read as unsigned integers.
+__device__ inline unsigned long long f64_key(double v) { return (unsigned long long)__double_as_longlong(v); }
+__device__ inline double key_f64(unsigned long long k) { return __longlong_as_double((long long)k); }
+
+// minimum and maximum of the calling waves' values into two LDS words: DPP inside the wave, one
+// atomic per wave on the bit patterns (mx >= 0)
+__device__ inline void minmax_to_lds(double mn, double mx, unsigned long long *slot)
+{
+    wave_minmax(mn, mx);
+    if ((threadIdx.x & 63) == 0) {
+        atomicMin(&slot[0], f64_key(mn));
+        atomicMax(&slot[1], f64_key(mx));
+    }
+}
+
+// Rank (position in sorted order, ties by index) of every element of a short list (len <=
+// kSelDirect); the elements of the wanted ranks are stored to sel.  THREADS / kSelDirect threads
+// share one element, each comparing it with a slice of the list (a single thread walking the
+// whole list would wait for one LDS round trip after the other); the partial ranks meet in
+// `counters`, which must be zero on entry.  list_visible: a barrier already lies between the
+// writes of the list and this call.
 template <int THREADS>
 __device__ inline void rank_directly(const double *list, int len, int below, int r_lo, int r_hi, double *sel,
-                                     unsigned *counters /* kSelDirect, scratch */)
+                                     unsigned *counters, bool list_visible)
 {
-    constexpr int PARTS = THREADS / kSelDirect;           // threads per element
+    constexpr int PARTS = THREADS / kSelDirect;             // threads per element
     constexpr int SLICE = (kSelDirect + PARTS - 1) / PARTS; // list entries per thread
     static_assert(PARTS >= 1 && PARTS * kSelDirect == THREADS, "THREADS is a multiple of kSelDirect");
     const int tid = threadIdx.x;
     const int e = tid % kSelDirect, part = tid / kSelDirect;
-    if (part == 0) counters[e] = 0;
-    __syncthreads();
+    if (!list_visible) __syncthreads();
     double v = 0.0;
     if (e < len) {
         v = list[e];
@@ -144,18 +169,8 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
     static_assert(THREADS % 64 == 0 && THREADS >= 256 && THREADS <= 1024, "one bucket per thread, at most 16 waves");
     constexpr int NW = THREADS / 64;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    if (Pp <= kSelDirect) { // the whole set is small: no buckets, no gathering
-        rank_directly<THREADS>(sh.pr, Pp, 0, r_lo, r_hi, sh.sel, reinterpret_cast<unsigned *>(sh.S));
-        return; // the caller's barrier publishes sel
-    }
-    // scratch inside S (free by now): [hist: THREADS u32][misc: 16 u32][wave totals: 16 u32][min/max keys: 4 u64][list: kSelDirect f64]
-    unsigned *hist = reinterpret_cast<unsigned *>(sh.S);
-    unsigned *misc = hist + THREADS; // 0: list length, 1: bucket of r_lo, 2: bucket of r_hi, 3: values below the bucket of r_lo, 4: its count
-    unsigned *wsum = misc + 16;
-    unsigned long long *mm = reinterpret_cast<unsigned long long *>(wsum + 16); // 0: min, 1: max, 2: min (second use), 3: max
-    double *list = reinterpret_cast<double *>(mm + 4);
-    static_assert((THREADS + 32) % 2 == 0 && (THREADS + 32) / 2 + 4 + kSelDirect <= kMaxPairsFull, "scratch fits in S, 8-byte aligned");
     const unsigned long long kmax = ~0ull;
+    const double inf = __builtin_huge_val();
 
     // every thread owns up to two values
     const double e0 = (tid < Pp) ? sh.pr[tid] : 0.0;
@@ -163,39 +178,22 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
     bool act0 = tid < Pp, act1 = tid + THREADS < Pp;
     int below = 0; // values known to be smaller than the whole active set
     int cnt = Pp;  // size of the active set
-    const double inf = __builtin_huge_val();
-
-    // minimum and maximum of the calling threads' values: DPP inside the wave, one LDS atomic per
-    // wave on the bit patterns, one barrier.  slot: 0 or 2 (alternating, so that a slot can be
-    // re-initialised behind the barrier of the other one's use)
-    auto block_minmax = [&](double mn, double mx, int slot, double &a, double &b) {
-        wave_minmax(mn, mx);
-        if (lane == 0) {
-            atomicMin(&mm[slot], f64_key(mn));
-            atomicMax(&mm[slot + 1], f64_key(fmax(mx, 0.0)));
-        }
-        __syncthreads();
-        a = key_f64(mm[slot]);
-        b = key_f64(mm[slot + 1]);
-    };
 
     for (int level = 0; level < 12; ++level) {
         const int slot = (level & 1) * 2;
-        hist[tid] = 0;
-        if (tid < 16) misc[tid] = (tid == 0) ? 0u : 0xFFFFFFFFu;
-        if (tid == 0) { // the other slot, for the next use
-            mm[2 - slot] = kmax;
-            mm[3 - slot] = 0ull;
-        }
-        if (level == 0) { // (later levels find their slot prepared by the level before)
-            if (tid == 0) {
-                mm[0] = kmax;
-                mm[1] = 0ull;
+        if (level > 0) {
+            // refine: clear what the previous level used (its last reads lie behind the barrier at
+            // its end), find the range of the narrowed set
+            sh.hist[tid] = 0;
+            if (tid < 16) sh.misc[tid] = (tid == 0) ? 0u : 0xFFFFFFFFu;
+            if (tid == 0) { // the other slot, for the level after this one
+                sh.mm[2 - slot] = kmax;
+                sh.mm[3 - slot] = 0ull;
             }
+            minmax_to_lds(fmin(act0 ? e0 : inf, act1 ? e1 : inf), fmax(act0 ? e0 : 0.0, act1 ? e1 : 0.0), &sh.mm[slot]);
             __syncthreads();
         }
-        double a, b;
-        block_minmax(fmin(act0 ? e0 : inf, act1 ? e1 : inf), fmax(act0 ? e0 : 0.0, act1 ? e1 : 0.0), slot, a, b);
+        const double a = key_f64(sh.mm[slot]), b = key_f64(sh.mm[slot + 1]);
         if (!(a < b)) { // all active values equal (or nothing rankable): both ranks are a
             if (tid == 0) {
                 sh.sel[0] = a;
@@ -210,59 +208,54 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
             return k < 0 ? 0 : (k > THREADS - 1 ? THREADS - 1 : k);
         };
         const int k0 = act0 ? bucket(e0) : 0, k1 = act1 ? bucket(e1) : 0;
-        if (act0) atomicAdd(&hist[k0], 1u);
-        if (act1) atomicAdd(&hist[k1], 1u);
+        if (act0) atomicAdd(&sh.hist[k0], 1u);
+        if (act1) atomicAdd(&sh.hist[k1], 1u);
         __syncthreads();
         // inclusive prefix sum of the bucket counts: DPP inside the wave, wave totals through LDS
-        const unsigned mine = hist[tid];
+        const unsigned mine = sh.hist[tid];
         unsigned incl = wave_inclusive_scan(mine);
-        if (lane == 63) wsum[wave] = incl;
+        if (lane == 63) sh.wsum[wave] = incl;
         __syncthreads();
         unsigned before = 0;
 #pragma unroll
-        for (int w = 0; w < NW; ++w) before += (w < wave) ? wsum[w] : 0u;
+        for (int w = 0; w < NW; ++w) before += (w < wave) ? sh.wsum[w] : 0u;
         incl += before;
         const unsigned excl = incl - mine;
         // the buckets holding the wanted ranks (ranks relative to the active set)
         const unsigned q_lo = (unsigned)(r_lo - below), q_hi = (unsigned)(r_hi - below);
         if (mine > 0 && excl <= q_lo && q_lo < incl) {
-            misc[1] = (unsigned)tid;
-            misc[3] = excl;
-            misc[4] = mine;
+            sh.misc[1] = (unsigned)tid;
+            sh.misc[3] = excl;
+            sh.misc[4] = mine;
         }
-        if (mine > 0 && excl <= q_hi && q_hi < incl) misc[2] = (unsigned)tid;
+        if (mine > 0 && excl <= q_hi && q_hi < incl) sh.misc[2] = (unsigned)tid;
         __syncthreads();
-        const unsigned b_lo = misc[1], b_hi = misc[2];
-        if (b_lo == 0xFFFFFFFFu || b_hi == 0xFFFFFFFFu) { // unrankable input: give up with a
-            if (tid == 0) {
-                sh.sel[0] = a;
-                sh.sel[1] = a;
-            }
-            return;
-        }
+        const unsigned b_lo = sh.misc[1], b_hi = sh.misc[2];
+        if (b_lo == 0xFFFFFFFFu || b_hi == 0xFFFFFFFFu) break; // unrankable input
         if (b_lo != b_hi) {
-            // adjacent ranks in different buckets: the largest value of the one, the smallest of the other
+            // adjacent ranks in different buckets: the largest value of the one, the smallest of the
+            // other (the other min/max slot is prepared and unused at this point)
             double mx = 0.0, mn = inf;
             if (act0 && (unsigned)k0 == b_lo) mx = fmax(mx, e0);
             if (act1 && (unsigned)k1 == b_lo) mx = fmax(mx, e1);
             if (act0 && (unsigned)k0 == b_hi) mn = fmin(mn, e0);
             if (act1 && (unsigned)k1 == b_hi) mn = fmin(mn, e1);
-            double lo_v, hi_v;
-            block_minmax(mn, mx, 2 - slot, hi_v, lo_v);
+            minmax_to_lds(mn, mx, &sh.mm[2 - slot]);
+            __syncthreads();
             if (tid == 0) {
-                sh.sel[0] = lo_v;
-                sh.sel[1] = hi_v;
+                sh.sel[0] = key_f64(sh.mm[3 - slot]);
+                sh.sel[1] = key_f64(sh.mm[2 - slot]);
             }
             return;
         }
-        below += (int)misc[3];
-        cnt = (int)misc[4];
+        below += (int)sh.misc[3];
+        cnt = (int)sh.misc[4];
         act0 = act0 && (unsigned)k0 == b_lo;
         act1 = act1 && (unsigned)k1 == b_lo;
         if (cnt <= kSelDirect) { // gather the bucket into a list and rank it
-            if (act0) list[atomicAdd(&misc[0], 1u)] = e0;
-            if (act1) list[atomicAdd(&misc[0], 1u)] = e1;
-            rank_directly<THREADS>(list, cnt, below, r_lo, r_hi, sh.sel, hist);
+            if (act0) sh.list[atomicAdd(&sh.misc[0], 1u)] = e0;
+            if (act1) sh.list[atomicAdd(&sh.misc[0], 1u)] = e1;
+            rank_directly<THREADS>(sh.list, cnt, below, r_lo, r_hi, sh.sel, sh.counters, false);
             return;
         }
         __syncthreads(); // all reads of misc, hist and wsum are done before the next level clears them
@@ -274,23 +267,33 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
 }
 
 // From the reduced pair sums in sh.S[0 .. n(n+1)/2) to h, K and the coefficient tables.  Called by
-// all THREADS threads of a workgroup (2 * THREADS >= n(n-1)/2 rounded up to a power of two), which
-// have written sh.S before (no barrier needed in between).  coef_lds, if not null, receives C [n*n] and rho [n] as well (LDS of the caller);
-// on return the writes to it still need a barrier.
+// all THREADS threads of a workgroup (n(n-1)/2 <= 2 * THREADS), which have written sh.S before (no
+// barrier needed in between).  coef_lds, if not null, receives C [n*n] and rho [n] as well (LDS of
+// the caller); on return the writes to it still need a barrier.  Returns h (in every thread).
 template <int THREADS>
-__device__ inline void bandwidth_from_sums(BwShared &sh, int n, int mode, double h_fixed,
+__device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, double h_fixed,
                                            DevState *__restrict__ st, float *__restrict__ coef,
                                            float *coef_lds)
 {
-    static_assert(THREADS % 64 == 0, "whole waves");
+    static_assert(THREADS % 64 == 0 && THREADS <= 1024, "whole waves, one histogram bucket per thread");
     const int tid = threadIdx.x;
     const int Pp = n * (n - 1) / 2;
+    const bool select = h_fixed <= 0.0 && Pp > 0;
+    const bool buckets = select && Pp > kSelDirect; // the selection will work with buckets
+    // the selection's scratch in its initial state (see select_two_ranks)
     if (tid < 2) sh.sel[tid] = 0.0;
+    if (tid < kSelDirect) sh.counters[tid] = 0;
+    if (buckets) {
+        sh.hist[tid] = 0;
+        if (tid < 16) sh.misc[tid] = (tid == 0) ? 0u : 0xFFFFFFFFu;
+        if (tid < 4) sh.mm[tid] = (tid & 1) ? 0ull : ~0ull;
+    }
     __syncthreads();
 
     // d2 per pair: direct sums, or S_ii + S_jj - 2 S_ij (clamped at 0) from the centred Gram.
     // Thread p takes pair p: row i is the largest one whose first pair index, i (2n - i - 1) / 2,
     // does not exceed p (estimate from the quadratic, then corrected).
+    double dmin = __builtin_huge_val(), dmax = 0.0;
     for (int p = tid; p < Pp; p += THREADS) {
         const float tn = (float)(2 * n - 1);
         int i = (int)(0.5f * (tn - sqrtf(fmaxf(tn * tn - 8.0f * (float)p, 0.0f))));
@@ -306,7 +309,10 @@ __device__ inline void bandwidth_from_sums(BwShared &sh, int n, int mode, double
         }
         if (!(d > 0.0)) d = 0.0; // clamps rounding negatives (and -0.0, and NaN)
         sh.pr[p] = d;
+        dmin = fmin(dmin, d);
+        dmax = fmax(dmax, d);
     }
+    if (buckets) minmax_to_lds(dmin, dmax, &sh.mm[0]); // the range of all values, for the first level
     __syncthreads();
 
     // Median of the multiset of all n*n entries of d2: n diagonal zeros plus every pair value
@@ -314,30 +320,35 @@ __device__ inline void bandwidth_from_sums(BwShared &sh, int n, int mode, double
     // pair value otherwise; an even count averages positions n*n/2 - 1 and n*n/2.  So what is
     // needed are the pair values of rank r_lo and r_hi (equal or adjacent), not a sorted list.
     const int t_lo = (n * n - 1) / 2, t_hi = (n * n) / 2; // t_hi >= n for every n >= 2
-    if (h_fixed <= 0.0 && Pp > 0) {
+    if (select) {
         // n = 2: position t_lo is one of the diagonal zeros - the other rank is selected twice
-        select_two_ranks<THREADS>(sh, Pp, (t_lo >= n) ? (t_lo - n) / 2 : (t_hi - n) / 2, (t_hi - n) / 2);
+        const int r_lo = (t_lo >= n) ? (t_lo - n) / 2 : (t_hi - n) / 2, r_hi = (t_hi - n) / 2;
+        if (buckets) select_two_ranks<THREADS>(sh, Pp, r_lo, r_hi);
+        else rank_directly<THREADS>(sh.pr, Pp, 0, r_lo, r_hi, sh.sel, sh.counters, true);
     }
     __syncthreads();
-    if (tid == 0) {
-        double med = 0.5 * ((t_lo >= n ? sh.sel[0] : 0.0) + sh.sel[1]);
-        double h = (h_fixed > 0.0) ? h_fixed : med / log((double)n + 1.0);
-        if (!(h > 0.0)) h = 1.0;
-        sh.h = h;
-        st->h = h;
+    if (tid == 0) { // one thread derives h (a logarithm and two divisions in fp64), LDS hands it on
+        const double med = 0.5 * ((t_lo >= n ? sh.sel[0] : 0.0) + sh.sel[1]);
+        double hh = (h_fixed > 0.0) ? h_fixed : med / log((double)n + 1.0);
+        if (!(hh > 0.0)) hh = 1.0;
+        sh.h = hh;
+        st->h = hh;
         st->med = med;
         // a single particle has no repulsive term at all: make that exact (phi = g)
-        st->two_over_h = (n == 1) ? 0.f : (float)(2.0 / h);
+        st->two_over_h = (n == 1) ? 0.f : (float)(2.0 / hh);
         st->n = n;
     }
     __syncthreads();
     const double h = sh.h;
     const double c2h = (n == 1) ? 0.0 : 2.0 / h;
     const double inv_n = 1.0 / (double)n;
+    const double neg_inv_h = -1.0 / h;
 
-    for (int e = tid; e < Pp; e += THREADS) sh.S[e] = exp(-sh.pr[e] / h); // K per pair, reusing S
+    for (int e = tid; e < Pp; e += THREADS) sh.S[e] = exp(sh.pr[e] * neg_inv_h); // K per pair, reusing S
     __syncthreads();
-    for (int i = tid >> 6; i < n; i += THREADS / 64) {   // wave -> row, lane -> column
+    // K, C, row sums: wave -> row, lane -> column.  K_ij and K_ji are the same LDS entry, so K is
+    // exactly symmetric; the diagonal is exactly 1.
+    for (int i = tid >> 6; i < n; i += THREADS / 64) {
         double r = 0.0;
         for (int j = tid & 63; j < n; j += 64) {
             const double k = (i == j) ? 1.0 : sh.S[i < j ? pair_index(i, j, n) : pair_index(j, i, n)];
@@ -353,6 +364,7 @@ __device__ inline void bandwidth_from_sums(BwShared &sh, int n, int mode, double
             if (coef_lds) coef_lds[n * n + i] = rho;
         }
     }
+    return h;
 }
 
 // A short list of partials (at most kDirectMaxFloats values, P <= kBwThreads) is summed by this

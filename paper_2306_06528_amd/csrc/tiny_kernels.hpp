@@ -62,9 +62,9 @@ __global__ __launch_bounds__(kTinyThreads) void step_tiny_kernel(float *__restri
     }
 
     // pass 2
-    bandwidth_from_sums<kTinyThreads>(sh, N, kModeDiff, h_fixed, st, coef, cl);
+    const double h = bandwidth_from_sums<kTinyThreads>(sh, N, kModeDiff, h_fixed, st, coef, cl);
     __syncthreads();
-    const float c2h = (N == 1) ? 0.f : (float)(2.0 / sh.h);
+    const float c2h = (N == 1) ? 0.f : (float)(2.0 / h);
 
     if constexpr (WHAT == kTinyBandwidth) return;
 
