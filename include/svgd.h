@@ -129,6 +129,22 @@ int svgd_phi_ld(svgd_handle_t h, const float *X, const float *G, int n, int64_t 
                 float *PHI, void *stream);
 
 /*
+ * svgd_step for particles that are n separately allocated vectors (App. B.2: the leader gathers
+ * every particle's parameters and gradients, each particle's own flat vector, before it forms
+ * the pairwise terms; here they are used where they lie, no copy into one matrix).  X_rows and
+ * G_rows are HOST arrays of n DEVICE pointers: X_rows[i] is particle i's D parameters, G_rows[i]
+ * its D scores (fp32, 4-byte aligned, any spacing or order; the 2n vectors must not overlap).
+ * The arrays are read during the call and need not outlive it.  Plain step: bandwidth from the
+ * median (or svgd_set_bandwidth), pair sums recomputed from X; carried sums are neither used nor
+ * left behind.  Same results as svgd_step on the packed matrix, at somewhat lower speed (every
+ * row has its own alignment, so stores are re-aligned per row and nothing is streamed past the
+ * caches).  INVALID_ARG: null or misaligned row pointer, overlapping rows; otherwise as svgd_step.
+ * Does not synchronise or allocate.
+ */
+int svgd_step_rows(svgd_handle_t h, float *const *X_rows, const float *const *G_rows, int n, int64_t D,
+                   float eps, void *stream);
+
+/*
  * Copy the bandwidth and kernel matrix (App. B.2: the per-pair kernel values, which the paper's
  * routine reads back one by one) of the most recent svgd_bandwidth/svgd_step/svgd_phi call
  * to HOST memory: *h_out (nullable) receives h; K_host (nullable, row-major) receives K and must

@@ -33,6 +33,24 @@ struct DevState {
     int n;
 };
 
+// Particles given as n separate rows (svgd_step_rows): where row i of X and of G starts, in floats
+// relative to row 0 of the same array, and the misalignment of X's row i against a 128-byte line.
+// Kernels compiled with ROWS = true take row addresses from this table instead of i * ld.
+struct RowTable {
+    int64_t x[kMaxN];
+    int64_t g[kMaxN];
+    int32_t ri[kMaxN]; // (address of X row i / 4) mod 32
+};
+// The table travels as a kernel argument (by value: nothing to allocate, copy or keep alive);
+// kernels compiled with ROWS = false take this stand-in instead and never read it.
+struct NoRows {
+    int64_t x[1];
+    int64_t g[1];
+    int32_t ri[1];
+};
+template <bool ROWS> struct RowArg { typedef NoRows type; };
+template <> struct RowArg<true> { typedef RowTable type; };
+
 // Offsets (in floats) into the handle's coefficient block.
 //   C   [n*n]   C_ij = K_ij / n
 //   RHO [n]     rho_i = (2/h) * (sum_j K_ij) / n

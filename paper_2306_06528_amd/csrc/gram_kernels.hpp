@@ -61,9 +61,10 @@ __device__ __forceinline__ void pair_accumulate(f32x4 (&x)[N], float (&acc)[N * 
     }
 }
 
-template <int N>
+template <int N, bool ROWS = false>
 __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict__ X, int64_t D, int64_t ld,
-                                                        float *__restrict__ partials)
+                                                        float *__restrict__ partials,
+                                                        typename RowArg<ROWS>::type rt)
 {
     constexpr int P = N * (N + 1) / 2;
     float acc[P];
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
             const int64_t col = (grp + u * nthreads) << 2; // past the end: every load is masked to 0
             const bool full = (col + 4 <= D);
 #pragma unroll
-            for (int j = 0; j < N; ++j) x[u][j] = load4(X + (int64_t)j * ld, col, D, full);
+            for (int j = 0; j < N; ++j) x[u][j] = load4(X + (ROWS ? rt.x[ROWS ? j : 0] : (int64_t)j * ld), col, D, full);
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) pair_accumulate<N>(x[u], acc);
@@ -116,15 +117,16 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
 // ---------------------------------------------------------------------------------------------
 constexpr int kGramWaves = 4; // waves per workgroup; adjacent 64-column slabs -> 1 KiB per row
 
-template <int NB>
+template <int NB, bool ROWS = false>
 __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float *__restrict__ X, int n,
-                                                                    int64_t D, int64_t ld, float *__restrict__ partials)
+                                                                    int64_t D, int64_t ld, float *__restrict__ partials,
+                                                                    typename RowArg<ROWS>::type rt)
 {
-    constexpr int ROWS = 16 * NB;
+    constexpr int NROW = 16 * NB;
     constexpr int RPL = 4 * NB; // rows per lane while loading
     constexpr int NPAIR = NB * (NB + 1) / 2;
     constexpr int TW = 64 * kGramWaves; // columns per workgroup tile
-    __shared__ float lds[kGramWaves][ROWS * 64];
+    __shared__ float lds[kGramWaves][NROW * 64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int q = lane >> 4, c16 = lane & 15;
@@ -137,6 +139,11 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
 
     const int64_t ntile = (D + TW - 1) / TW;
     f32x4 x[RPL];
+    int64_t xro[ROWS ? RPL : 1]; // where this lane's rows start (separate rows only)
+    if constexpr (ROWS) {
+#pragma unroll
+        for (int i = 0; i < RPL; ++i) xro[i] = (4 * i + q < n) ? rt.x[ROWS ? 4 * i + q : 0] : 0;
+    }
     auto load_slab = [&](int64_t tile) {
         const int64_t wcol = tile * TW + (wave << 6);
         const int64_t col = wcol + 4 * c16;
@@ -144,7 +151,7 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int row = 4 * i + q;
-            x[i] = (row < n) ? load4(X + (int64_t)row * ld, col, D, full) : f32x4{0.f, 0.f, 0.f, 0.f};
+            x[i] = (row < n) ? load4(X + (ROWS ? xro[ROWS ? i : 0] : (int64_t)row * ld), col, D, full) : f32x4{0.f, 0.f, 0.f, 0.f};
         }
     };
     if ((int64_t)blockIdx.x < ntile) load_slab(blockIdx.x);
@@ -194,7 +201,7 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
 
     // combine the waves through LDS, then store the upper triangle in tri(i, j) order
     __syncthreads();
-    float *xch = &lds[0][0]; // [wave-1][pair][r][lane], NPAIR*256 floats per wave (<= ROWS*64)
+    float *xch = &lds[0][0]; // [wave-1][pair][r][lane], NPAIR*256 floats per wave (<= NROW*64)
     if (wave > 0) {
 #pragma unroll
         for (int p = 0; p < NPAIR; ++p)

@@ -1,6 +1,7 @@
 // Host side of the C ABI declared in include/svgd.h: handle, argument validation, launches.
 #include "../../include/svgd.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <mutex>
@@ -132,17 +133,29 @@ bool overlaps(const float *a, const float *b, int n, int64_t D, int64_t ld)
     return pa < pb + bytes && pb < pa + bytes;
 }
 
+// rt != nullptr: the particles are separate rows (svgd_step_rows); the table goes along by value
 template <int N>
-void launch_gram_valu(const float *X, int64_t D, int64_t ld, float *partials, int grid, hipStream_t s)
+void launch_gram_valu(const float *X, int64_t D, int64_t ld, float *partials, int grid, hipStream_t s,
+                      const RowTable *rt)
 {
-    gram_valu_kernel<N><<<grid, 256, 0, s>>>(X, D, ld, partials);
+    if (rt)
+        gram_valu_kernel<N, true><<<grid, 256, 0, s>>>(X, D, ld, partials, *rt);
+    else
+        gram_valu_kernel<N, false><<<grid, 256, 0, s>>>(X, D, ld, partials, NoRows{});
 }
 
 template <int N, bool EMIT, bool CARRY>
 void launch_update_valu(float *X, const float *G, float *PHI, const float *coef, const DevState *st,
-                        int64_t D, int64_t ld, float eps, float *gram_out, int grid, hipStream_t s)
+                        int64_t D, int64_t ld, float eps, float *gram_out, int grid, hipStream_t s,
+                        const RowTable *rt)
 {
-    update_valu_kernel<N, EMIT, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out);
+    if constexpr (!EMIT && !CARRY) {
+        if (rt) {
+            update_valu_kernel<N, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, *rt);
+            return;
+        }
+    }
+    update_valu_kernel<N, EMIT, CARRY, false><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, NoRows{});
 }
 
 #define SVGD_SWITCH_N(n, CALL)                                                                     \
@@ -175,7 +188,8 @@ int max_parts(const svgd_ctx *c, int n)
 
 // Passes 1 and 2: Gram partials -> fp64 reduction -> h, K, coefficient tables (all on `s`).
 // With use_carry the partials the previous update left in c->partials stand in for pass 1.
-int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld, hipStream_t s, bool use_carry)
+int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld, hipStream_t s, bool use_carry,
+                      const RowTable *rt = nullptr)
 {
     const int P = n * (n + 1) / 2;
     const int cap_parts = max_parts(c, n);
@@ -188,7 +202,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
         nparts = clampi((ngroups + 255) / 256, 1, mini(c->num_cu * 3, cap_parts)); // all resident at once; each ends with a reduction
         mode = (n <= 8) ? kModeDiff : kModeGram;
         KernelTimer t(c, SVGD_KERNEL_GRAM, s);
-#define CALL(N) launch_gram_valu<N>(X, D, ld, c->partials, nparts, s)
+#define CALL(N) launch_gram_valu<N>(X, D, ld, c->partials, nparts, s, rt)
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
     } else {
@@ -197,14 +211,16 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
         nparts = clampi(ntile, 1, mini(c->num_cu * 2, cap_parts));
         mode = kModeGram;
         const int NB = (n + 15) / 16;
-        if (NB == 1)
-            gram_mfma_kernel<1><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials);
-        else if (NB == 2)
-            gram_mfma_kernel<2><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials);
-        else if (NB == 3)
-            gram_mfma_kernel<3><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials);
-        else
-            gram_mfma_kernel<4><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials);
+#define GRAM(NBV)                                                                                            \
+    do {                                                                                                     \
+        if (rt) gram_mfma_kernel<NBV, true><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, *rt); \
+        else gram_mfma_kernel<NBV, false><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}); \
+    } while (0)
+        if (NB == 1) GRAM(1);
+        else if (NB == 2) GRAM(2);
+        else if (NB == 3) GRAM(3);
+        else GRAM(4);
+#undef GRAM
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
@@ -233,7 +249,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
 // the update also leaves the Gram partials of the new X in c->partials.
 template <bool EMIT, bool CARRY>
 int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D, int64_t ld, float eps,
-               hipStream_t s)
+               hipStream_t s, const RowTable *rt = nullptr)
 {
     KernelTimer t(c, SVGD_KERNEL_UPDATE, s);
     if (n <= kValuMaxN) {
@@ -242,7 +258,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int per_cu = CARRY ? 2 : 8;
         const int grid = clampi((ngroups + 255) / 256, 1, mini(c->num_cu * per_cu, CARRY ? max_parts(c, n) : kMaxParts));
         if (CARRY) c->carry_nparts = grid;
-#define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, ld, eps, c->partials, grid, s)
+#define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, ld, eps, c->partials, grid, s, rt)
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
     } else {
@@ -256,13 +272,15 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         if (CARRY) c->carry_nparts = grid; // one partial per workgroup, the tail's included
         // rows that all start on a 128-byte boundary (X's and G's) need no re-aligned stores and
         // can be read with streaming loads
-        const bool aligned = !EMIT && rows_aligned(X, ld) && rows_aligned(G, ld);
+        const bool aligned = !EMIT && !rt && rows_aligned(X, ld) && rows_aligned(G, ld);
 #define UPD(NBV, FULL)                                                                                       \
     do {                                                                                                     \
-        if (!EMIT && aligned)                                                                                \
-            update_mfma_kernel<NBV, false, FULL, CARRY, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials); \
+        if (!EMIT && !CARRY && rt)                                                                           \
+            update_mfma_kernel<NBV, false, FULL, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, *rt); \
+        else if (!EMIT && aligned)                                                                           \
+            update_mfma_kernel<NBV, false, FULL, CARRY, true, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}); \
         else                                                                                                 \
-            update_mfma_kernel<NBV, EMIT, FULL, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials);       \
+            update_mfma_kernel<NBV, EMIT, FULL, CARRY, false, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}); \
     } while (0)
         if (n == 16) UPD(1, true);
         else if (NB == 1) UPD(1, false);
@@ -539,6 +557,45 @@ int svgd_step_ld(svgd_handle_t c, float *X, const float *G, int n, int64_t D, in
 int svgd_step(svgd_handle_t c, float *X, const float *G, int n, int64_t D, float eps, void *stream)
 {
     return svgd_step_ld(c, X, G, n, D, D, eps, stream);
+}
+
+int svgd_step_rows(svgd_handle_t c, float *const *X_rows, const float *const *G_rows, int n, int64_t D, float eps,
+                   void *stream)
+{
+    int rc = check_handle(c);
+    if (rc) return rc;
+    if (!X_rows || !G_rows || !std::isfinite(eps)) return SVGD_ERR_INVALID_ARG;
+    rc = check_shape(c, n, D, D);
+    if (rc) return rc;
+    // every row: non-null, 4-byte aligned; no two of the 2n rows may overlap
+    struct Span { uintptr_t lo, hi; };
+    Span spans[2 * SVGD_MAX_PARTICLES];
+    const uintptr_t bytes = (uintptr_t)D * sizeof(float);
+    for (int i = 0; i < n; ++i) {
+        const uintptr_t px = (uintptr_t)X_rows[i], pg = (uintptr_t)G_rows[i];
+        if (!px || !pg || (px & 3) || (pg & 3)) return SVGD_ERR_INVALID_ARG;
+        spans[2 * i] = {px, px + bytes};
+        spans[2 * i + 1] = {pg, pg + bytes};
+    }
+    std::sort(spans, spans + 2 * n, [](const Span &a, const Span &b) { return a.lo < b.lo; });
+    for (int i = 1; i < 2 * n; ++i)
+        if (spans[i].lo < spans[i - 1].hi) return SVGD_ERR_INVALID_ARG;
+    // row starts relative to row 0 (float pointers are 4-byte aligned, so the differences are whole floats)
+    RowTable rt;
+    for (int i = 0; i < kMaxN; ++i) {
+        const int k = i < n ? i : 0;
+        rt.x[i] = (int64_t)(((intptr_t)X_rows[k] - (intptr_t)X_rows[0]) / (intptr_t)sizeof(float));
+        rt.g[i] = (int64_t)(((intptr_t)G_rows[k] - (intptr_t)G_rows[0]) / (intptr_t)sizeof(float));
+        rt.ri[i] = (int32_t)(((uintptr_t)X_rows[k] >> 2) & 31u);
+    }
+    DeviceGuard guard(c->device);
+    hipStream_t s = (hipStream_t)stream;
+    c->carry_valid = false; // the partials buffer is about to be overwritten; nothing is carried for separate rows
+    float *X = X_rows[0];
+    const float *G = G_rows[0];
+    rc = run_kernel_matrix(c, X, n, D, D, s, false, &rt);
+    if (rc) return rc;
+    return run_update<false, false>(c, X, G, nullptr, n, D, D, eps, s, &rt);
 }
 
 int svgd_phi_ld(svgd_handle_t c, const float *X, const float *G, int n, int64_t D, int64_t ld, float *PHI,

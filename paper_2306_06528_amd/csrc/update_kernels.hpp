@@ -22,15 +22,17 @@ namespace svgd {
 // n <= kValuMaxN (12): vector ALU, lanes = columns, 4 consecutive columns per thread (16-byte
 // loads, 1 KiB contiguous per row per wave).  C and rho are wave-uniform: LDS broadcasts.
 // ---------------------------------------------------------------------------------------------
-template <int N, bool EMIT, bool CARRY>
+template <int N, bool EMIT, bool CARRY, bool ROWS = false>
 __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
                                                           const float *__restrict__ G,
                                                           float *__restrict__ PHI,
                                                           const float *__restrict__ coef,
                                                           const DevState *__restrict__ st,
                                                           int64_t D, int64_t ld, float eps,
-                                                          float *__restrict__ gram_out)
+                                                          float *__restrict__ gram_out,
+                                                          typename RowArg<ROWS>::type rt)
 {
+    static_assert(!(ROWS && (EMIT || CARRY)), "separate rows: plain in-place step only");
     static_assert(!(CARRY && EMIT), "the pair sums are carried only when X is updated");
     // CARRY: the pair sums of the UPDATED columns, in the format of gram_valu_kernel<N>
     constexpr bool kDiff = (N <= 8);
@@ -57,8 +59,8 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
         f32x4 x[N], z[N];
 #pragma unroll
         for (int j = 0; j < N; ++j) {
-            x[j] = load4(X + (int64_t)j * ld, col, D, full);
-            z[j] = load4_stream(G + (int64_t)j * ld, col, D, full);
+            x[j] = load4(X + (ROWS ? rt.x[ROWS ? j : 0] : (int64_t)j * ld), col, D, full);
+            z[j] = load4_stream(G + (ROWS ? rt.g[ROWS ? j : 0] : (int64_t)j * ld), col, D, full);
         }
 
         f32x4 m = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -79,7 +81,7 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
                 store4(PHI + (int64_t)i * ld, col, D, full, acc);
             } else {
                 const f32x4 xn = x[i] + eps * acc;
-                store4(X + (int64_t)i * ld, col, D, full, xn);
+                store4(X + (ROWS ? rt.x[ROWS ? i : 0] : (int64_t)i * ld), col, D, full, xn);
                 if constexpr (CARRY) y[i] = xn - m; // columns beyond D: x = g = 0 -> xn = 0, m = 0
             }
         }
@@ -151,11 +153,12 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 constexpr int kUpdCur = 16 * 64;    // floats per wave
 constexpr int kUpdCarry = 64 * 32;  // floats per wave
 
-template <bool EMIT, bool CARRY>
+template <bool EMIT, bool CARRY, bool ROWS>
 __device__ inline void update_tail_columns(float *__restrict__ X, const float *__restrict__ G,
                                            float *__restrict__ OUT, const float *__restrict__ coef,
                                            float c2h, int n, int64_t D, int64_t ld, int64_t col0, float eps,
-                                           float *__restrict__ lds, float *__restrict__ gram_out)
+                                           float *__restrict__ lds, float *__restrict__ gram_out,
+                                           const typename RowArg<ROWS>::type &rt)
 {
     // plain per-column evaluation for the < 64 columns after the last full tile
     float *zs = lds, *xs = lds + 64 * 64, *yn = lds + 2 * 64 * 64;
@@ -164,8 +167,8 @@ __device__ inline void update_tail_columns(float *__restrict__ X, const float *_
     for (int j = part; j < n; j += 4) {
         float xv = 0.f, gv = 0.f;
         if (ok) {
-            xv = X[(int64_t)j * ld + col0 + col];
-            gv = G[(int64_t)j * ld + col0 + col];
+            xv = X[(ROWS ? rt.x[ROWS ? j : 0] : (int64_t)j * ld) + col0 + col];
+            gv = G[(ROWS ? rt.g[ROWS ? j : 0] : (int64_t)j * ld) + col0 + col];
         }
         xs[j * 64 + col] = xv;
         zs[j * 64 + col] = gv - c2h * xv;
@@ -182,7 +185,7 @@ __device__ inline void update_tail_columns(float *__restrict__ X, const float *_
         const float xv = xs[i * 64 + col];
         const float phi = fmaf(coef[kOffRho + i], xv, acc);
         const float out = EMIT ? phi : fmaf(eps, phi, xv);
-        if (ok) OUT[(int64_t)i * ld + col0 + col] = out;
+        if (ok) OUT[(ROWS ? rt.x[ROWS ? i : 0] : (int64_t)i * ld) + col0 + col] = out;
         if constexpr (CARRY) yn[i * 64 + col] = ok ? out - m : 0.f;
     }
     if constexpr (CARRY) {
@@ -218,13 +221,17 @@ __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 // steady-state tile), which lets the scheduler fill the MFMA shadows; a handful of wave-uniform
 // branches inside the tile made it 20-30 % slower when tried.  The first tile of a range, which
 // has to mask its left edge, is a separate, branchy instance of the same code.
-template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false>
+// ROWS: the particles are n separately allocated rows; row addresses (and store alignments) come
+// from a RowTable instead of i * ld (plain in-place step only, re-aligned stores).
+template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false, bool ROWS = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
                         const float *__restrict__ coef, const DevState *__restrict__ st, int n,
-                        int64_t D, int64_t ld, float eps, float *__restrict__ gram_out)
+                        int64_t D, int64_t ld, float eps, float *__restrict__ gram_out,
+                        typename RowArg<ROWS>::type rt)
 {
     static_assert(!(CARRY && EMIT), "the Gram is carried only when X is updated");
+    static_assert(!(ROWS && (EMIT || CARRY || ALIGNED)), "separate rows: plain in-place step, re-aligned stores");
     constexpr int NS = 4 * NB; // contraction steps = rows per lane
     constexpr int NPAIR = NB * (NB + 1) / 2;
     // [A operands: NB*NB*64 float4][4 waves x (cur + carry)]
@@ -245,7 +252,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 for (int p = threadIdx.x; p < P; p += 256) tail_out[p] = 0.f;
         }
         if ((nfull << 6) < D)
-            update_tail_columns<EMIT, CARRY>(X, G, OUT, coef, c2h, n, D, ld, nfull << 6, eps, lds, tail_out);
+            update_tail_columns<EMIT, CARRY, ROWS>(X, G, OUT, coef, c2h, n, D, ld, nfull << 6, eps, lds, tail_out, rt);
         return;
     }
 
@@ -307,12 +314,30 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     const int64_t c_begin = t0 << 6;
 
     // lane part of every load address: row 4q, column 4c; the rest is wave-uniform
-    const int64_t in_lane = (int64_t)(4 * q) * ld + 4 * c16;
+    const int64_t in_lane = ROWS ? (int64_t)(4 * c16) : (int64_t)(4 * q) * ld + 4 * c16;
     // stores: lane (rl = q, p = c16) writes row urow + q; a row's misalignment in floats is
     // (a0 + row * dm) mod 32 because every tile starts at a multiple of 32 columns
-    const int64_t out_lane = (int64_t)q * ld + 4 * c16;
+    const int64_t out_lane = ROWS ? (int64_t)(4 * c16) : (int64_t)q * ld + 4 * c16;
     const uint32_t dm = (uint32_t)ld & 31u;
     const uint32_t a0 = (uint32_t)(reinterpret_cast<uintptr_t>(OUT) >> 2) & 31u;
+    // separate rows: where this lane's rows of X and G start (loads), and for every row where it
+    // starts and how it is aligned (stores; in LDS, read per store group)
+    int64_t xro[ROWS ? NS : 1], gro[ROWS ? NS : 1];
+    __shared__ int64_t srow[ROWS ? kMaxN : 1];
+    __shared__ int sri[ROWS ? kMaxN : 1];
+    if constexpr (ROWS) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s) {
+            const int row = 16 * (s >> 2) + (s & 3) + 4 * q;
+            xro[s] = (row < n) ? rt.x[ROWS ? row : 0] : 0;
+            gro[s] = (row < n) ? rt.g[ROWS ? row : 0] : 0;
+        }
+        if (threadIdx.x < kMaxN) {
+            srow[threadIdx.x] = ((int)threadIdx.x < n) ? rt.x[ROWS ? threadIdx.x : 0] : 0;
+            sri[threadIdx.x] = ((int)threadIdx.x < n) ? rt.ri[ROWS ? threadIdx.x : 0] : 0;
+        }
+        __syncthreads();
+    }
 
     // Software pipeline across tiles: the loads of tile t+1 are issued while tile t is being
     // multiplied.  Schedules chosen by measurement:
@@ -345,19 +370,19 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     };
     auto load_x = [&](const float *xt, int s) __attribute__((always_inline)) {
         const int urow = 16 * (s >> 2) + (s & 3); // uniform part of the row index
-        if (FULLROWS || urow + 4 * q < n) x[s] = load16x(xt + (int64_t)urow * ld);
+        if (FULLROWS || urow + 4 * q < n) x[s] = load16x(xt + (ROWS ? xro[ROWS ? s : 0] : (int64_t)urow * ld));
     };
     auto load_g = [&](const float *gt, int s) __attribute__((always_inline)) {
         const int urow = 16 * (s >> 2) + (s & 3);
-        if (FULLROWS || urow + 4 * q < n) z[s] = load16g(gt + (int64_t)urow * ld);
+        if (FULLROWS || urow + 4 * q < n) z[s] = load16g(gt + (ROWS ? gro[ROWS ? s : 0] : (int64_t)urow * ld));
     };
     auto load_next = [&](const float *xt, const float *gt) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
             const int urow = 16 * (s >> 2) + (s & 3);
             if (FULLROWS || urow + 4 * q < n) {
-                if constexpr (XBUF) xn[s] = load16x(xt + (int64_t)urow * ld);
-                if constexpr (GBUF) gn[s] = load16g(gt + (int64_t)urow * ld);
+                if constexpr (XBUF) xn[s] = load16x(xt + (ROWS ? xro[ROWS ? s : 0] : (int64_t)urow * ld));
+                if constexpr (GBUF) gn[s] = load16g(gt + (ROWS ? gro[ROWS ? s : 0] : (int64_t)urow * ld));
             }
         }
     };
@@ -423,7 +448,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             const int urow = 16 * b + 4 * k;     // uniform part of the row index
             const int rloc = 4 * k + qv;         // row within the block
             const int row = urow + qv;
-            const int ri = (int)((a0 + (uint32_t)row * dm) & 31u);
+            const int ri = ROWS ? sri[ROWS ? row : 0] : (int)((a0 + (uint32_t)row * dm) & 31u);
             const int o0 = 4 * c16 - ri;         // window offset relative to the tile start
             f32x4 v;
 #pragma unroll
@@ -432,7 +457,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : cur_index(rloc, o)];
             }
             if (FULLROWS || row < n) {
-                float *dst = ot + (int64_t)urow * ld - ri;
+                float *dst = ot + (ROWS ? srow[ROWS ? row : 0] : (int64_t)urow * ld) - ri;
                 if constexpr (!FIRST) {
                     __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(dst));
                 } else { // left end of the range: nothing left of c_begin is ours
@@ -543,9 +568,9 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         const int64_t c_end = t1 << 6;
         for (int idx = lane; idx < 16 * NB * 32; idx += 64) {
             const int row = idx >> 5, cc = idx & 31;
-            const int ri = (int)((a0 + (uint32_t)row * dm) & 31u);
+            const int ri = ROWS ? sri[ROWS ? row : 0] : (int)((a0 + (uint32_t)row * dm) & 31u);
             if (row < n && cc >= 32 - ri && c_end - 32 + cc >= c_begin)
-                OUT[(int64_t)row * ld + c_end - 32 + cc] = carry[row * 32 + cc];
+                OUT[(ROWS ? srow[ROWS ? row : 0] : (int64_t)row * ld) + c_end - 32 + cc] = carry[row * 32 + cc];
         }
     }
 

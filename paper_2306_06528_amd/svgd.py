@@ -34,6 +34,9 @@ _lib.svgd_step_ld.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int
                               ctypes.c_int64, ctypes.c_float, ctypes.c_void_p]
 _lib.svgd_phi_ld.argtypes = [_H, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64,
                              ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+_lib.svgd_step_rows.argtypes = [_H, ctypes.POINTER(ctypes.c_void_p), ctypes.POINTER(ctypes.c_void_p), ctypes.c_int,
+                                ctypes.c_int64, ctypes.c_float, ctypes.c_void_p]
+_lib.svgd_step_rows.restype = ctypes.c_int
 _lib.svgd_get_last.argtypes = [_H, ctypes.POINTER(ctypes.c_double), ctypes.c_void_p, ctypes.c_void_p]
 _lib.svgd_destroy.argtypes = [_H]
 _lib.svgd_diag_copy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p]
@@ -219,6 +222,25 @@ class Svgd:
         n, D, ld = shape
         self._check(_lib.svgd_step_ld(self._h, X.data_ptr(), G.data_ptr(), n, D, ld, float(eps),
                                       _stream_ptr(stream)))
+        self._last_n = n
+
+    def step_rows(self, X_rows, G_rows, eps: float, stream=None):
+        """svgd_step_rows: the particles are n separately allocated 1-D float32 CUDA tensors of equal
+        length (X_rows[i], updated in place) with their scores (G_rows[i]); nothing is copied."""
+        n = len(X_rows)
+        if n < 1 or len(G_rows) != n:
+            raise ValueError("X_rows and G_rows must be non-empty sequences of the same length")
+        D = X_rows[0].numel()
+        for name, rows in (("X_rows", X_rows), ("G_rows", G_rows)):
+            for t in rows:
+                if not (isinstance(t, torch.Tensor) and t.dtype is torch.float32 and t.is_cuda and t.dim() == 1
+                        and t.numel() == D and (D == 1 or t.stride(0) == 1)):
+                    raise TypeError(f"{name} must hold contiguous 1-D float32 CUDA tensors of one length")
+                if t.get_device() != self._device:
+                    raise ValueError(f"a row of {name} is on cuda:{t.get_device()}, the handle on cuda:{self._device}")
+        xp = (ctypes.c_void_p * n)(*[t.data_ptr() for t in X_rows])
+        gp = (ctypes.c_void_p * n)(*[t.data_ptr() for t in G_rows])
+        self._check(_lib.svgd_step_rows(self._h, xp, gp, n, D, float(eps), _stream_ptr(stream)))
         self._last_n = n
 
     def phi(self, X, G, PHI, stream=None):
