@@ -147,6 +147,9 @@ def main():
     ap.add_argument("--separate-gram", action="store_true",
                     help="run the pairwise-d2 pass as its own kernel every step instead of carrying "
                          "the sums over from the previous update (SVGD_FLAG_CARRY_GRAM)")
+    ap.add_argument("--fuse", action="store_true",
+                    help="SVGD_FLAG_FUSE_MFMA: the single-launch fused step also for 13 <= n <= 32 "
+                         "(measured slower than two launches there; for the record)")
     ap.add_argument("--dense-rows", action="store_true",
                     help="rows D floats apart (ld = D) instead of ld = D rounded up to 32 floats")
     ap.add_argument("--swag", action="store_true",
@@ -256,6 +259,8 @@ def main():
 
     carry = not args.separate_gram
     flags = svgd.FLAG_CARRY_GRAM if carry else 0
+    if args.fuse:
+        flags |= svgd.FLAG_FUSE_MFMA
     # the timed region: K steps, the dominant kernel (update) timed by events inside it
     dt, prof_upd, recs_upd = timed(flags, X, G, kinds=("update",))
     # the same K steps again: with every kernel timed (the per-kernel breakdown), with one event
@@ -321,7 +326,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{wl.cfg.name}: n={n} particles x D={D} fp32, rows {ld} floats apart, eps={eps}",
                    "n": n, "D": D, "ld": ld, "config_index": args.config,
-                   "gram": "carried from the previous update" if carry else "separate pass"},
+                   "gram": "carried from the previous update" if carry else "separate pass",
+                   "fuse_mfma": bool(args.fuse)},
         "step_hbm_frac": (UPDATE_BYTES_PER_PARAM if carry else STEP_BYTES_PER_PARAM) * n * D
                          / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "kernel_ms": kern_ms,

@@ -57,19 +57,28 @@ enum svgd_status {
  * closing remarks: a particle is updated only after the whole kernel matrix of the previous
  * iterate exists).  With this flag svgd_step, while it still holds every updated column on chip,
  * also accumulates the pairwise sums of the NEW X, and the next svgd_step on the same (X, n, D)
- * skips its own pass over X.  The caller promises that between two svgd_step calls X is modified
+ * skips its own pass over X (and, when the list of carried sums is short - small and medium
+ * problems - runs as a single kernel launch).  The caller promises that between two svgd_step calls X is modified
  * by nobody else; after touching X (or to be safe) call svgd_forget_carry.  svgd_bandwidth and
  * svgd_phi always recompute from X and drop the carried sums, and so does a svgd_step on another
  * stream than the step that produced them.
  */
 #define SVGD_FLAG_CARRY_GRAM 1u
+/*
+ * With carried sums, a step whose list of carried partial sums is short runs as ONE kernel launch
+ * (the update kernel derives h and K itself, in every workgroup) - by default only on the
+ * vector-ALU path, n <= 12, where that measures faster than two launches.  This flag extends it to
+ * 13 <= n <= 32, where it measures slower (one launch of 15 us against two launches in 12 us at
+ * n = 16, D = 8,577): for measurements, and for callers to whom the launch count matters more.
+ */
+#define SVGD_FLAG_FUSE_MFMA 2u
 
 /*
  * Create a handle for problems up to max_n particles (1..SVGD_MAX_PARTICLES) of up to max_D
  * parameters each on HIP device `device_id` (-1 = the current device); the sizes play the part of
  * the paper's `num_particles` and of the flattened parameter count of its networks (App. B.2, the
  * arguments of the top-level SVGD inference call; its `lengthscale` is svgd_set_bandwidth, its
- * `lr` the eps of svgd_step).  `flags` is 0 or SVGD_FLAG_CARRY_GRAM.  Allocates the handle's
+ * `lr` the eps of svgd_step).  `flags`: 0 or an OR of the SVGD_FLAG_* values above.  Allocates the handle's
  * device scratch: 8192 * max_n * (max_n + 1) / 2 bytes of partial sums (17 MB at max_n = 64) and
  * about 0.2 MB of tables.  On success *out receives the handle.
  */
@@ -161,9 +170,10 @@ int svgd_get_last(svgd_handle_t h, double *h_out, float *K_host, void *stream);
  * kernel kind k, then switches recording off.  At most 2048 launches are recorded per session;
  * the events are created by svgd_profile_begin*, none while recording.
  * Not every kind runs in every step: a short list of partial sums is reduced inside the
- * BANDWIDTH kernel (no REDUCE launch), carried pair sums replace the GRAM pass, and problems with
- * n <= 8 and n * D <= 16384 run as one kernel, which is counted as UPDATE (as BANDWIDTH when
- * svgd_bandwidth launches it).
+ * BANDWIDTH kernel (no REDUCE launch), carried pair sums replace the GRAM pass, a short list of
+ * carried sums at n <= 32 is consumed by the UPDATE kernel itself (the whole step is then that one
+ * launch), and problems with n <= 8 and n * D <= 16384 run as one kernel, which is counted as
+ * UPDATE (as BANDWIDTH when svgd_bandwidth launches it).
  */
 enum svgd_kernel_kind {
     SVGD_KERNEL_GRAM = 0,      /* pairwise-d2 partial sums (pass over X) */

@@ -269,11 +269,13 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
 // From the reduced pair sums in sh.S[0 .. n(n+1)/2) to h, K and the coefficient tables.  Called by
 // all THREADS threads of a workgroup (n(n-1)/2 <= 2 * THREADS), which have written sh.S before (no
 // barrier needed in between).  coef_lds, if not null, receives C [n*n] and rho [n] as well (LDS of
-// the caller); on return the writes to it still need a barrier.  Returns h (in every thread).
+// the caller); on return the writes to it still need a barrier.  write_global = false: st and coef
+// (device memory) are left alone - for workgroups that repeat the computation of another one.
+// Returns h (in every thread).
 template <int THREADS>
 __device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, double h_fixed,
                                            DevState *__restrict__ st, float *__restrict__ coef,
-                                           float *coef_lds)
+                                           float *coef_lds, bool write_global = true)
 {
     static_assert(THREADS % 64 == 0 && THREADS <= 1024, "whole waves, one histogram bucket per thread");
     const int tid = threadIdx.x;
@@ -332,11 +334,13 @@ __device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, doub
         double hh = (h_fixed > 0.0) ? h_fixed : med / log((double)n + 1.0);
         if (!(hh > 0.0)) hh = 1.0;
         sh.h = hh;
-        st->h = hh;
-        st->med = med;
-        // a single particle has no repulsive term at all: make that exact (phi = g)
-        st->two_over_h = (n == 1) ? 0.f : (float)(2.0 / hh);
-        st->n = n;
+        if (write_global) {
+            st->h = hh;
+            st->med = med;
+            // a single particle has no repulsive term at all: make that exact (phi = g)
+            st->two_over_h = (n == 1) ? 0.f : (float)(2.0 / hh);
+            st->n = n;
+        }
     }
     __syncthreads();
     const double h = sh.h;
@@ -353,17 +357,76 @@ __device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, doub
         for (int j = tid & 63; j < n; j += 64) {
             const double k = (i == j) ? 1.0 : sh.S[i < j ? pair_index(i, j, n) : pair_index(j, i, n)];
             r += k;
-            coef[kOffK + i * n + j] = (float)k;
-            coef[kOffC + i * n + j] = (float)(k * inv_n);
+            if (write_global) {
+                coef[kOffK + i * n + j] = (float)k;
+                coef[kOffC + i * n + j] = (float)(k * inv_n);
+            }
             if (coef_lds) coef_lds[i * n + j] = (float)(k * inv_n);
         }
         r = wave_sum_f64(r); // row sum of K
         if ((tid & 63) == 0) {
             const float rho = (float)(c2h * r * inv_n);
-            coef[kOffRho + i] = rho;
+            if (write_global) coef[kOffRho + i] = rho;
             if (coef_lds) coef_lds[n * n + i] = rho;
         }
     }
+    return h;
+}
+
+// The whole of pass 2 as the prologue of an update kernel (fused step): every workgroup sums the
+// short list of partials that the previous update left behind and derives h, K, C and rho for
+// itself, C [n*n] and rho [n] into coef_lds (LDS of the caller, barrier included); the workgroup
+// with write_global also records them in st and coef for svgd_get_last.  Returns h.  THREADS
+// threads, n <= 32 (n(n-1)/2 <= 2 * THREADS).  A workgroup costs what the bandwidth kernel costs, but
+// all of them run at once and the launch, with its gap, is gone.
+template <int THREADS>
+__device__ inline double kernel_matrix_prologue(BwShared &sh, const float *__restrict__ partials, int nparts, int n,
+                                                int mode, double h_fixed, DevState *__restrict__ st,
+                                                float *__restrict__ coef, float *coef_lds, bool write_global)
+{
+    const int P = n * (n + 1) / 2;
+    constexpr int U = 16; // loads in flight per thread
+    if (2 * P <= THREADS) {
+        // few pairs: thread (kk, pp) = (tid / P, tid % P), kk < KL, sums the partials kk, kk + KL, ...
+        // of entry pp (consecutive threads read consecutive floats); the KL sums of an entry meet
+        // in LDS (sh.pr is not in use yet)
+        const int KL = THREADS / P < 32 ? THREADS / P : 32;
+        const int tid = threadIdx.x, kk = tid / P, pp = tid - kk * P;
+        double s = 0.0;
+        if (kk < KL) {
+            for (int k = kk; k < nparts; k += U * KL) {
+                float v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int ku = k + u * KL;
+                    v[u] = partials[(int64_t)(ku < nparts ? ku : nparts - 1) * P + pp];
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) s += (k + u * KL < nparts) ? (double)v[u] : 0.0;
+            }
+            sh.pr[tid] = s;
+        }
+        __syncthreads();
+        if (tid < P) {
+            double t = 0.0;
+            for (int q = 0; q < KL; ++q) t += sh.pr[q * P + tid];
+            sh.S[tid] = t;
+        }
+    } else {
+        for (int pp = threadIdx.x; pp < P; pp += THREADS) { // consecutive threads read consecutive floats
+            double s = 0.0;
+            for (int k = 0; k < nparts; k += U) {
+                float v[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) v[u] = partials[(int64_t)(k + u < nparts ? k + u : nparts - 1) * P + pp];
+#pragma unroll
+                for (int u = 0; u < U; ++u) s += (k + u < nparts) ? (double)v[u] : 0.0;
+            }
+            sh.S[pp] = s;
+        }
+    }
+    const double h = bandwidth_from_sums<THREADS>(sh, n, mode, h_fixed, st, coef, coef_lds, write_global);
+    __syncthreads();
     return h;
 }
 

@@ -41,6 +41,7 @@ struct svgd_ctx {
     int64_t carry_D;
     int64_t carry_ld;
     int carry_nparts;
+    int64_t carry_off;        // where in `partials` the carried list starts (floats): 0 or the upper half
     hipStream_t carry_stream; // the stream the carried sums were produced on
     int64_t partials_cap;     // floats available in `partials`
     int last_n; // 0 = nothing computed yet
@@ -145,17 +146,24 @@ void launch_gram_valu(const float *X, int64_t D, int64_t ld, float *partials, in
 }
 
 template <int N, bool EMIT, bool CARRY>
-void launch_update_valu(float *X, const float *G, float *PHI, const float *coef, const DevState *st,
+void launch_update_valu(float *X, const float *G, float *PHI, float *coef, DevState *st,
                         int64_t D, int64_t ld, float eps, float *gram_out, int grid, hipStream_t s,
                         const RowTable *rt)
 {
     if constexpr (!EMIT && !CARRY) {
         if (rt) {
-            update_valu_kernel<N, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, *rt);
+            update_valu_kernel<N, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, *rt, FusedArgs{});
             return;
         }
     }
-    update_valu_kernel<N, EMIT, CARRY, false><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, NoRows{});
+    update_valu_kernel<N, EMIT, CARRY, false><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, NoRows{}, FusedArgs{});
+}
+
+template <int N>
+void launch_update_valu_fused(float *X, const float *G, float *coef, DevState *st, int64_t D, int64_t ld, float eps,
+                              float *gram_out, int grid, hipStream_t s, const FusedArgs &fa)
+{
+    update_valu_kernel<N, false, true, false, true><<<grid, 256, 0, s>>>(X, G, nullptr, coef, st, D, ld, eps, gram_out, NoRows{}, fa);
 }
 
 #define SVGD_SWITCH_N(n, CALL)                                                                     \
@@ -194,8 +202,10 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
     const int P = n * (n + 1) / 2;
     const int cap_parts = max_parts(c, n);
     int nparts, mode;
+    const float *partials = c->partials; // where the list of partials for pass 2 starts
     if (use_carry) {
         nparts = c->carry_nparts;
+        partials += c->carry_off;
         mode = (n <= 8) ? kModeDiff : kModeGram; // the update kernels mirror the Gram kernels' formats
     } else if (n <= kValuMaxN) {
         const int64_t ngroups = (D + 3) / 4;
@@ -229,15 +239,14 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
     const bool direct = P <= kBwThreads && (int64_t)nparts * P <= kDirectMaxFloats;
     if (!direct) {
         KernelTimer t(c, SVGD_KERNEL_REDUCE, s);
-        reduce_partials_kernel<<<dim3((P + 255) / 256, kSlices), 256, 0, s>>>(c->partials, nparts, P,
-                                                                             c->part2);
+        reduce_partials_kernel<<<dim3((P + 255) / 256, kSlices), 256, 0, s>>>(partials, nparts, P, c->part2);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
     {
         KernelTimer t(c, SVGD_KERNEL_BANDWIDTH, s);
-        bandwidth_kernel<<<1, kBwThreads, 0, s>>>(c->part2, direct ? c->partials : nullptr, nparts, n,
-                                                  mode, c->h_fixed, c->state, c->coef);
+        bandwidth_kernel<<<1, kBwThreads, 0, s>>>(c->part2, direct ? partials : nullptr, nparts, n, mode, c->h_fixed,
+                                                  c->state, c->coef);
     }
     e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
@@ -255,9 +264,13 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
     if (n <= kValuMaxN) {
         const int64_t ngroups = (D + 3) / 4;
         // fewer, longer-lived workgroups when each one ends with a reduction of its pair sums
-        const int per_cu = CARRY ? 2 : 8;
+        // (with the pair sums of 9 to 12 particles in registers only one workgroup fits a CU)
+        const int per_cu = CARRY ? (n <= 8 ? 2 : 1) : 8;
         const int grid = clampi((ngroups + 255) / 256, 1, mini(c->num_cu * per_cu, CARRY ? max_parts(c, n) : kMaxParts));
-        if (CARRY) c->carry_nparts = grid;
+        if (CARRY) {
+            c->carry_nparts = grid;
+            c->carry_off = 0;
+        }
 #define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, ld, eps, c->partials, grid, s, rt)
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
@@ -269,18 +282,21 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         const int max_workers = mini(c->num_cu, (CARRY ? max_parts(c, n) : kMaxParts) - 1);
         const int grid = clampi((nfull + 3) / 4, 1, max_workers) + 1;
         const int NB = (n + 15) / 16;
-        if (CARRY) c->carry_nparts = grid; // one partial per workgroup, the tail's included
+        if (CARRY) { // one partial per workgroup, the tail's included
+            c->carry_nparts = grid;
+            c->carry_off = 0;
+        }
         // rows that all start on a 128-byte boundary (X's and G's) need no re-aligned stores and
         // can be read with streaming loads
         const bool aligned = !EMIT && !rt && rows_aligned(X, ld) && rows_aligned(G, ld);
 #define UPD(NBV, FULL)                                                                                       \
     do {                                                                                                     \
         if (!EMIT && !CARRY && rt)                                                                           \
-            update_mfma_kernel<NBV, false, FULL, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, *rt); \
+            update_mfma_kernel<NBV, false, FULL, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, *rt, FusedArgs{}); \
         else if (!EMIT && aligned)                                                                           \
-            update_mfma_kernel<NBV, false, FULL, CARRY, true, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}); \
+            update_mfma_kernel<NBV, false, FULL, CARRY, true, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, FusedArgs{}); \
         else                                                                                                 \
-            update_mfma_kernel<NBV, EMIT, FULL, CARRY, false, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}); \
+            update_mfma_kernel<NBV, EMIT, FULL, CARRY, false, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, FusedArgs{}); \
     } while (0)
         if (n == 16) UPD(1, true);
         else if (NB == 1) UPD(1, false);
@@ -294,6 +310,72 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail(c, e);
+    return SVGD_OK;
+}
+
+// The fused step: one launch that starts with pass 2 in every workgroup (from the partials the
+// previous update left at carry_off), updates X and leaves the partials of the new X in the other
+// half of the scratch.  For short lists only: every workgroup reads the whole list.
+// Every workgroup sums the whole list with its 256 threads - by groups of threads when there are few
+// pairs (see kernel_matrix_prologue) - so what bounds the prologue is the number of partials one
+// thread adds up, one dependent batch of 16 loads after the other.
+constexpr int kFusedMaxChain = 160;
+
+bool can_fuse(const svgd_ctx *c, int n)
+{
+    const int64_t P = (int64_t)n * (n + 1) / 2, half = (c->partials_cap / 2) & ~(int64_t)63;
+    // On the matrix-core path (n > 12) the prologue runs with one wave per SIMD and measured slower
+    // than the two launches it replaces (n = 16, D = 8,577: 15.1 against 12.4 us per step): only on request.
+    const int max_n = (c->flags & SVGD_FLAG_FUSE_MFMA) ? 32 : kValuMaxN;
+    if (n > max_n || (int64_t)c->carry_nparts * P > half) return false;
+    int64_t chain;
+    if (2 * P <= 256) {
+        const int64_t KL = 256 / P < 32 ? 256 / P : 32;
+        chain = (c->carry_nparts + KL - 1) / KL;
+    } else {
+        chain = (int64_t)c->carry_nparts * ((P + 255) / 256);
+    }
+    return chain <= kFusedMaxChain;
+}
+
+int run_update_fused(svgd_ctx *c, float *X, const float *G, int n, int64_t D, int64_t ld, float eps, hipStream_t s)
+{
+    KernelTimer t(c, SVGD_KERNEL_UPDATE, s);
+    const int64_t P = (int64_t)n * (n + 1) / 2, half = (c->partials_cap / 2) & ~(int64_t)63;
+    const FusedArgs fa{c->partials + c->carry_off, c->carry_nparts, c->h_fixed};
+    const int64_t out_off = c->carry_off == 0 ? half : 0;
+    float *gram_out = c->partials + out_off;
+    const int cap = (int)(half / P < kMaxParts ? half / P : kMaxParts); // partials that fit into a half
+    int grid;
+    if (n <= kValuMaxN) {
+        const int64_t ngroups = (D + 3) / 4;
+        // all workgroups resident at once (9 to 12 particles: one per CU), or the prologue is paid twice
+        grid = clampi((ngroups + 255) / 256, 1, mini(c->num_cu * (n <= 8 ? 2 : 1), cap));
+#define CALL(N) launch_update_valu_fused<N>(X, G, c->coef, c->state, D, ld, eps, gram_out, grid, s, fa)
+        SVGD_SWITCH_N(n, CALL)
+#undef CALL
+    } else {
+        const int64_t nfull = D / 64;
+        grid = clampi((nfull + 3) / 4, 1, mini(c->num_cu, cap - 1)) + 1;
+        const bool aligned = rows_aligned(X, ld) && rows_aligned(G, ld);
+#define UPD(NBV, FULL)                                                                                       \
+    do {                                                                                                     \
+        if (aligned)                                                                                         \
+            update_mfma_kernel<NBV, false, FULL, true, true, false, true><<<grid, 256, 0, s>>>(X, G, nullptr, c->coef, c->state, n, D, ld, eps, gram_out, NoRows{}, fa); \
+        else                                                                                                 \
+            update_mfma_kernel<NBV, false, FULL, true, false, false, true><<<grid, 256, 0, s>>>(X, G, nullptr, c->coef, c->state, n, D, ld, eps, gram_out, NoRows{}, fa); \
+    } while (0)
+        if (n == 16) UPD(1, true);
+        else if (n < 16) UPD(1, false);
+        else if (n == 32) UPD(2, true);
+        else UPD(2, false);
+#undef UPD
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(c, e);
+    c->carry_nparts = grid;
+    c->carry_off = out_off;
+    c->last_n = n;
     return SVGD_OK;
 }
 
@@ -385,6 +467,7 @@ svgd_ctx *static_ctx(int dev, int *rc)
     c.carry_n = 0;
     c.carry_D = c.carry_ld = 0;
     c.carry_nparts = 0;
+    c.carry_off = 0;
     c.carry_stream = nullptr;
     c.last_n = 0;
     c.last_hip_error = 0;
@@ -407,7 +490,7 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
 {
     if (!out) return SVGD_ERR_INVALID_ARG;
     *out = nullptr;
-    if (max_n < 1 || max_D < 1 || (flags & ~(uint32_t)SVGD_FLAG_CARRY_GRAM) != 0 || device_id < -1)
+    if (max_n < 1 || max_D < 1 || (flags & ~(uint32_t)(SVGD_FLAG_CARRY_GRAM | SVGD_FLAG_FUSE_MFMA)) != 0 || device_id < -1)
         return SVGD_ERR_INVALID_ARG;
     if (max_n > SVGD_MAX_PARTICLES) return SVGD_ERR_TOO_LARGE;
 
@@ -424,6 +507,7 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
     c->carry_D = 0;
     c->carry_ld = 0;
     c->carry_nparts = 0;
+    c->carry_off = 0;
     c->carry_stream = nullptr;
     c->partials_cap = 0;
     c->last_n = 0;
@@ -540,10 +624,14 @@ int svgd_step_ld(svgd_handle_t c, float *X, const float *G, int n, int64_t D, in
                            c->carry_D == D && c->carry_ld == ld && c->carry_stream == s;
     c->carry_valid = false;
     if (is_tiny(n, D)) return run_tiny<kTinyStep>(c, X, G, nullptr, n, D, ld, eps, s);
-    rc = run_kernel_matrix(c, X, n, D, ld, s, use_carry);
-    if (rc) return rc;
-    if (!carry_mode) return run_update<false, false>(c, X, G, nullptr, n, D, ld, eps, s);
-    rc = run_update<false, true>(c, X, G, nullptr, n, D, ld, eps, s);
+    if (use_carry && can_fuse(c, n)) {
+        rc = run_update_fused(c, X, G, n, D, ld, eps, s); // the whole step in one launch
+    } else {
+        rc = run_kernel_matrix(c, X, n, D, ld, s, use_carry);
+        if (rc) return rc;
+        if (!carry_mode) return run_update<false, false>(c, X, G, nullptr, n, D, ld, eps, s);
+        rc = run_update<false, true>(c, X, G, nullptr, n, D, ld, eps, s);
+    }
     if (rc) return rc;
     c->carry_valid = true;
     c->carry_X = X;

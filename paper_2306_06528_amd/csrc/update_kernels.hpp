@@ -14,25 +14,39 @@
 #pragma once
 #include <type_traits>
 
+#include "bandwidth_kernels.hpp"
 #include "common.hpp"
 
 namespace svgd {
+
+// FUSED: the step in ONE launch.  The kernel starts with pass 2 (kernel_matrix_prologue: every
+// workgroup derives h, C and rho for itself from the short list of pair-sum partials that the
+// previous update left behind) and, being a CARRY kernel, ends by leaving the partials of the new
+// X for the next one - in the other half of the scratch, because workgroups that are still in
+// their prologue read the old list.  Used when that list is short (small problems, where two more
+// launches would cost as much as the work).
+struct FusedArgs {
+    const float *partials_in; // [nparts_in][n (n + 1) / 2], format of the Gram kernels
+    int nparts_in;
+    double h_fixed;
+};
 
 // ---------------------------------------------------------------------------------------------
 // n <= kValuMaxN (12): vector ALU, lanes = columns, 4 consecutive columns per thread (16-byte
 // loads, 1 KiB contiguous per row per wave).  C and rho are wave-uniform: LDS broadcasts.
 // ---------------------------------------------------------------------------------------------
-template <int N, bool EMIT, bool CARRY, bool ROWS = false>
+template <int N, bool EMIT, bool CARRY, bool ROWS = false, bool FUSED = false>
 __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
                                                           const float *__restrict__ G,
                                                           float *__restrict__ PHI,
-                                                          const float *__restrict__ coef,
-                                                          const DevState *__restrict__ st,
+                                                          float *__restrict__ coef,
+                                                          DevState *__restrict__ st,
                                                           int64_t D, int64_t ld, float eps,
                                                           float *__restrict__ gram_out,
-                                                          typename RowArg<ROWS>::type rt)
+                                                          typename RowArg<ROWS>::type rt, FusedArgs fa)
 {
     static_assert(!(ROWS && (EMIT || CARRY)), "separate rows: plain in-place step only");
+    static_assert(!FUSED || (CARRY && !ROWS), "the fused step lives on carried pair sums");
     static_assert(!(CARRY && EMIT), "the pair sums are carried only when X is updated");
     // CARRY: the pair sums of the UPDATED columns, in the format of gram_valu_kernel<N>
     constexpr bool kDiff = (N <= 8);
@@ -42,15 +56,23 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 #pragma unroll
         for (int p = 0; p < P; ++p) pacc[p] = 0.f;
     }
-    const float c2h = st->two_over_h;
     // C and rho are wave-uniform.  They are staged in LDS and read back as broadcasts: a chain of
     // dependent scalar loads from global memory costs microseconds per wave, which is all there
     // is to hide behind when D is small.
-    __shared__ __attribute__((aligned(16))) float C[N * N];
-    __shared__ float rho[N];
-    for (int e = threadIdx.x; e < N * N; e += 256) C[e] = coef[kOffC + e];
-    if (threadIdx.x < N) rho[threadIdx.x] = coef[kOffRho + threadIdx.x];
-    __syncthreads();
+    __shared__ __attribute__((aligned(16))) float C[N * N + N];
+    float *rho = C + N * N;
+    float c2h;
+    if constexpr (FUSED) {
+        __shared__ BwShared sh;
+        const double h = kernel_matrix_prologue<256>(sh, fa.partials_in, fa.nparts_in, N, kDiff ? kModeDiff : kModeGram,
+                                                     fa.h_fixed, st, coef, C, blockIdx.x == 0);
+        c2h = (N == 1) ? 0.f : (float)(2.0 / h);
+    } else {
+        c2h = st->two_over_h;
+        for (int e = threadIdx.x; e < N * N; e += 256) C[e] = coef[kOffC + e];
+        if (threadIdx.x < N) rho[threadIdx.x] = coef[kOffRho + threadIdx.x];
+        __syncthreads();
+    }
     const int64_t ngroups = (D + 3) >> 2;
     const int64_t nthreads = (int64_t)gridDim.x * 256;
     for (int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x; grp < ngroups; grp += nthreads) {
@@ -155,7 +177,7 @@ constexpr int kUpdCarry = 64 * 32;  // floats per wave
 
 template <bool EMIT, bool CARRY, bool ROWS>
 __device__ inline void update_tail_columns(float *__restrict__ X, const float *__restrict__ G,
-                                           float *__restrict__ OUT, const float *__restrict__ coef,
+                                           float *__restrict__ OUT, const float *Cm, const float *rhov,
                                            float c2h, int n, int64_t D, int64_t ld, int64_t col0, float eps,
                                            float *__restrict__ lds, float *__restrict__ gram_out,
                                            const typename RowArg<ROWS>::type &rt)
@@ -181,9 +203,9 @@ __device__ inline void update_tail_columns(float *__restrict__ X, const float *_
     }
     for (int i = part; i < n; i += 4) {
         float acc = 0.f;
-        for (int j = 0; j < n; ++j) acc = fmaf(coef[kOffC + i * n + j], zs[j * 64 + col], acc);
+        for (int j = 0; j < n; ++j) acc = fmaf(Cm[i * n + j], zs[j * 64 + col], acc);
         const float xv = xs[i * 64 + col];
-        const float phi = fmaf(coef[kOffRho + i], xv, acc);
+        const float phi = fmaf(rhov[i], xv, acc);
         const float out = EMIT ? phi : fmaf(eps, phi, xv);
         if (ok) OUT[(ROWS ? rt.x[ROWS ? i : 0] : (int64_t)i * ld) + col0 + col] = out;
         if constexpr (CARRY) yn[i * 64 + col] = ok ? out - m : 0.f;
@@ -223,13 +245,14 @@ __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 // has to mask its left edge, is a separate, branchy instance of the same code.
 // ROWS: the particles are n separately allocated rows; row addresses (and store alignments) come
 // from a RowTable instead of i * ld (plain in-place step only, re-aligned stores).
-template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false, bool ROWS = false>
+template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false, bool ROWS = false, bool FUSED = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
-                        const float *__restrict__ coef, const DevState *__restrict__ st, int n,
+                        float *__restrict__ coef, DevState *__restrict__ st, int n,
                         int64_t D, int64_t ld, float eps, float *__restrict__ gram_out,
-                        typename RowArg<ROWS>::type rt)
+                        typename RowArg<ROWS>::type rt, FusedArgs fa)
 {
+    static_assert(!FUSED || (CARRY && !ROWS && NB <= 2), "the fused step: carried pair sums, n <= 32");
     static_assert(!(CARRY && EMIT), "the Gram is carried only when X is updated");
     static_assert(!(ROWS && (EMIT || CARRY || ALIGNED)), "separate rows: plain in-place step, re-aligned stores");
     constexpr int NS = 4 * NB; // contraction steps = rows per lane
@@ -239,8 +262,23 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q = lane >> 4, c16 = lane & 15;
-    const float c2h = st->two_over_h;
     float *__restrict__ OUT = EMIT ? PHI : X;
+    // C (n x n) and rho (n): the handle's tables, or - fused step - this workgroup's own copies in
+    // LDS, computed by the prologue in the (still unused) staging area
+    __shared__ float cl[FUSED ? 32 * 32 + 32 : 1];
+    const float *Cm = coef + kOffC, *rhov = coef + kOffRho;
+    float c2h;
+    if constexpr (FUSED) {
+        static_assert(sizeof(BwShared) <= 4 * (kUpdCur + kUpdCarry) * sizeof(float), "pass 2 fits into the staging area");
+        BwShared &sh = *reinterpret_cast<BwShared *>(lds + NB * NB * 64 * 4);
+        const double h = kernel_matrix_prologue<256>(sh, fa.partials_in, fa.nparts_in, n, kModeGram, fa.h_fixed, st, coef,
+                                                     cl, blockIdx.x == 0);
+        c2h = (n == 1) ? 0.f : (float)(2.0 / h);
+        Cm = cl;
+        rhov = cl + n * n;
+    } else {
+        c2h = st->two_over_h;
+    }
 
     const int64_t nfull = D >> 6; // full 64-column tiles
     if (blockIdx.x == gridDim.x - 1) { // the extra workgroup: ragged tail only
@@ -252,7 +290,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 for (int p = threadIdx.x; p < P; p += 256) tail_out[p] = 0.f;
         }
         if ((nfull << 6) < D)
-            update_tail_columns<EMIT, CARRY, ROWS>(X, G, OUT, coef, c2h, n, D, ld, nfull << 6, eps, lds, tail_out, rt);
+            update_tail_columns<EMIT, CARRY, ROWS>(X, G, OUT, Cm, rhov, c2h, n, D, ld, nfull << 6, eps, lds, tail_out, rt);
         return;
     }
 
@@ -279,14 +317,14 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         const int i = 16 * bi + (l & 15), j0 = 16 * sg + 4 * (l >> 4);
         f32x4 v;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) v[k] = (i < n && j0 + k < n) ? coef[kOffC + i * n + j0 + k] : 0.f;
+        for (int k = 0; k < 4; ++k) v[k] = (i < n && j0 + k < n) ? Cm[i * n + j0 + k] : 0.f;
         As4[e] = v;
     }
     float rho[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s) {
         const int row = 16 * (s >> 2) + 4 * q + (s & 3);
-        rho[s] = (FULLROWS || row < n) ? coef[kOffRho + row] : 0.f;
+        rho[s] = (FULLROWS || row < n) ? rhov[row] : 0.f;
     }
     __syncthreads();
 

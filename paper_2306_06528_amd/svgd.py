@@ -69,6 +69,7 @@ for _f in ("svgd_create", "svgd_set_bandwidth", "svgd_bandwidth", "svgd_step", "
 
 SVGD_OK = 0
 FLAG_CARRY_GRAM = 1
+FLAG_FUSE_MFMA = 2
 KERNEL_KINDS = ("gram", "reduce", "bandwidth", "update")
 MAX_PARTICLES = 64
 STATIC_MAX_D = 1 << 32

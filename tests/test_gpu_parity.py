@@ -483,6 +483,28 @@ def test_carried_gram_matches_oracle_every_step(svgd, n, D, padded):
     check_carried_chain(svgd, X, G, 0.05, padded=padded, steps=4)
 
 
+@pytest.mark.parametrize("n,D", [(16, 8577), (13, 4099), (24, 20_011), (32, 8577), (32, 4096), (17, 1531), (8, 100_003)])
+def test_fused_single_launch_step_on_request(svgd, n, D):
+    """SVGD_FLAG_FUSE_MFMA: with a short list of carried sums the step is one launch also on the
+    matrix-core path (13 <= n <= 32) - seen in the launch counts - and its results match the oracle
+    like every other path."""
+    X, G = _random_problem(n, D, 7 * n + D, x_std=0.3)
+    eps = 0.05
+    with svgd.Svgd(n, D, flags=svgd.FLAG_CARRY_GRAM | svgd.FLAG_FUSE_MFMA) as eng:
+        eng.step(X, G, eps)                   # pairwise-d2 pass, bandwidth, update
+        eng.profile_begin()
+        for step in range(3):                 # each of these: the update kernel alone
+            Xh = X.cpu().numpy()
+            eng.step(X, G, eps)
+            h, K = eng.get_last(n)
+            ref = orc.step(Xh, G.cpu().numpy(), eps)
+            assert abs(h - ref["h"]) / ref["h"] <= TOL_H, f"step {step}"
+            assert np.abs(K - ref["K"]).max() <= TOL_K, f"step {step}"
+            assert_x_new(X.cpu().numpy(), ref, eps, f"step {step}")
+        prof = eng.profile_end()
+    assert [prof[k][1] for k in svgd.KERNEL_KINDS] == [0, 0, 0, 3]
+
+
 def test_carried_gram_is_dropped_when_it_must_be(svgd):
     n, D = 32, 10_007
     X, G = _random_problem(n, D, 77)
