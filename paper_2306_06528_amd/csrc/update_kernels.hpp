@@ -75,15 +75,30 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
     }
     const int64_t ngroups = (D + 3) >> 2;
     const int64_t nthreads = (int64_t)gridDim.x * 256;
-    for (int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x; grp < ngroups; grp += nthreads) {
-        const int64_t col = grp << 2;
-        const bool full = (col + 4 <= D);
-        f32x4 x[N], z[N];
+    // PREFETCH (carried pair sums of 9 to 12 particles, where the registers allow a single wave per
+    // SIMD anyway): the loads of a thread's next column group are issued as soon as this group's
+    // results are stored, before its pair sums are accumulated, so that arithmetic runs while the
+    // loads are in flight (88.6 instead of 94.3 us per step at n = 12, D = 3,000,000).  At n <= 8
+    // the longer live ranges cost a resident wave and the kernel gets slower.
+    constexpr bool PREFETCH = CARRY && N > 8;
+    f32x4 x[N], z[N];
+    auto load_group = [&](int64_t g) __attribute__((always_inline)) {
+        const int64_t c = g << 2;
+        const bool fl = (c + 4 <= D);
 #pragma unroll
         for (int j = 0; j < N; ++j) {
-            x[j] = load4(X + (ROWS ? rt.x[ROWS ? j : 0] : (int64_t)j * ld), col, D, full);
-            z[j] = load4_stream(G + (ROWS ? rt.g[ROWS ? j : 0] : (int64_t)j * ld), col, D, full);
+            x[j] = load4(X + (ROWS ? rt.x[ROWS ? j : 0] : (int64_t)j * ld), c, D, fl);
+            z[j] = load4_stream(G + (ROWS ? rt.g[ROWS ? j : 0] : (int64_t)j * ld), c, D, fl);
         }
+    };
+    const int64_t grp0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if constexpr (PREFETCH) {
+        if (grp0 < ngroups) load_group(grp0);
+    }
+    for (int64_t grp = grp0; grp < ngroups; grp += nthreads) {
+        const int64_t col = grp << 2;
+        const bool full = (col + 4 <= D);
+        if constexpr (!PREFETCH) load_group(grp);
 
         f32x4 m = f32x4{0.f, 0.f, 0.f, 0.f};
         if constexpr (CARRY && !kDiff) { // centre by the pre-update column mean
@@ -108,6 +123,9 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
             }
         }
         if constexpr (CARRY) {
+            if constexpr (PREFETCH) {
+                if (grp + nthreads < ngroups) load_group(grp + nthreads);
+            }
 #pragma unroll
             for (int i = 0; i < N; ++i) {
 #pragma unroll
