@@ -245,13 +245,15 @@ def main():
         best = None
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         reps = 10
-        for pattern in range(8):
+        # every variant both ways: always from the near end, and (pattern + 16 on every other call)
+        # alternating the direction as the steps of a CARRY_GRAM handle do
+        for pattern in [p + 16 * alt for p in range(12) for alt in (0, 1)]:
             for per_cu in (1, 2, 4, 8):
-                for _ in range(3):
-                    svgd.diag_axpy_rows(Xv, Gv, 0.0, pattern, cus * per_cu, stream=stream)
+                for i in range(4):
+                    svgd.diag_axpy_rows(Xv, Gv, 0.0, pattern ^ (16 * (i & 1) if pattern >= 16 else 0), cus * per_cu, stream=stream)
                 e0.record(stream)
-                for _ in range(reps):
-                    svgd.diag_axpy_rows(Xv, Gv, 0.0, pattern, cus * per_cu, stream=stream)
+                for i in range(reps):
+                    svgd.diag_axpy_rows(Xv, Gv, 0.0, pattern ^ (16 * (i & 1) if pattern >= 16 else 0), cus * per_cu, stream=stream)
                 e1.record(stream)
                 torch.cuda.synchronize()
                 ms = e0.elapsed_time(e1) / reps
@@ -357,8 +359,9 @@ def main():
             # the same bytes moved by a kernel that does nothing else (svgd_diag_axpy_rows on the
             # same X and G, in the same run): the practical ceiling, and the update against it
             "ceiling": ceiling["gbs"],
-            "ceiling_kernel": f"diag_axpy_rows_kernel<{ceiling['pattern']}>, {ceiling['workgroups']} workgroups, "
-                              f"{ceiling['ms']:.4f} ms",
+            "ceiling_kernel": f"svgd_diag_axpy_rows pattern {ceiling['pattern'] & 15}"
+                              f"{', direction alternating from call to call' if ceiling['pattern'] >= 16 else ''}, "
+                              f"{ceiling['workgroups']} workgroups, {ceiling['ms']:.4f} ms",
             "frac_of_ceiling": upd_gbs / ceiling["gbs"],
         },
     }

@@ -211,8 +211,12 @@ int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream);
  * 0 and 2: a wave instruction covers 4 rows x 256 bytes (the matrix-core update's shape), 1 and 3:
  * 1 KiB of one row (the vector-ALU update's shape), with 8 (patterns 0, 1) or 16 (2, 3) loads per
  * array in flight per lane; patterns 4..7 are 0..3 with the loads carrying the streaming
- * (no-allocate) hint as well as the stores; `workgroups` (1..65536) of 256 threads stride over the
- * column tiles.  Enqueued on `stream` of the current device; does not synchronise or allocate.
+ * (no-allocate) hint as well as the stores, 8..11 are 0..3 with that hint on the loads of G only
+ * (the update's own policy: X stays cacheable); adding 16 to a pattern walks the columns from the
+ * far end, so that calls which alternate p and p + 16 start each pass on what the previous one
+ * left in the memory-side cache, as successive steps of a CARRY_GRAM handle do.  Other values:
+ * SVGD_ERR_INVALID_ARG.  `workgroups` (1..65536) of 256 threads stride over the column tiles.
+ * Enqueued on `stream` of the current device; does not synchronise or allocate.
  */
 int svgd_diag_axpy_rows(float *X, const float *G, int n, int64_t D, int64_t ld, float s, int pattern,
                         int workgroups, void *stream);

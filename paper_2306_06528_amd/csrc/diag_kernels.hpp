@@ -23,13 +23,16 @@ __global__ __launch_bounds__(256) void diag_copy_kernel(const f32x4 *__restrict_
 //          tile).
 // U loads per array are in flight per lane (U * RPI rows); rows beyond n are clamped for the loads
 // and masked for the stores, so the steady state has no divergent branch.  The waves of a
-// workgroup take adjacent tiles; workgroups stride over the full tiles; the columns after the
-// last full tile are done element-wise by the last workgroup.  Stores carry the streaming hint,
-// as the update's do; NT: so do the loads (only sensible when no cache line is shared between
-// rows, i.e. rows that start on 128-byte boundaries).
-template <int PAT, int U, bool NT>
+// workgroup take adjacent tiles; workgroups stride over the full tiles (reverse: from the last
+// tile down, so that a caller alternating the direction starts each pass on what the previous one
+// left in the memory-side cache); the columns after the last full tile are done element-wise by
+// the last workgroup.  Stores carry the streaming hint, as the update's do; NT = 1: so do all
+// loads, NT = 2: so do the loads of G while X is loaded plainly, the update's policy (streaming
+// loads are only sensible when no cache line is shared between rows, i.e. rows that start on
+// 128-byte boundaries).
+template <int PAT, int U, int NT>
 __global__ __launch_bounds__(256) void diag_axpy_rows_kernel(float *__restrict__ X, const float *__restrict__ G,
-                                                             int n, int64_t D, int64_t ld, float s)
+                                                             int n, int64_t D, int64_t ld, float s, int reverse)
 {
     constexpr int TC = PAT == 0 ? 64 : 256;      // columns per wave tile
     constexpr int RPI = PAT == 0 ? 4 : 1;        // rows per wave instruction
@@ -38,7 +41,10 @@ __global__ __launch_bounds__(256) void diag_axpy_rows_kernel(float *__restrict__
     const int64_t nfull = D / TC;
     const int lrow = PAT == 0 ? q : 0;
     const int64_t lcol = PAT == 0 ? 4 * c16 : 4 * lane;
-    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < nfull; tile += (int64_t)gridDim.x * 4) {
+    const int64_t first = (int64_t)blockIdx.x * 4 + wave, stride = (int64_t)gridDim.x * 4;
+    const int64_t cnt = first < nfull ? (nfull - 1 - first) / stride + 1 : 0;
+    for (int64_t k = 0; k < cnt; ++k) {
+        const int64_t tile = first + (reverse ? cnt - 1 - k : k) * stride;
         const int64_t col = tile * TC + lcol;
         for (int r0 = 0; r0 < n; r0 += U * RPI) {
             f32x4 x[U], g[U];
@@ -46,13 +52,10 @@ __global__ __launch_bounds__(256) void diag_axpy_rows_kernel(float *__restrict__
             for (int u = 0; u < U; ++u) {
                 const int row = r0 + u * RPI + lrow;
                 const int64_t off = (int64_t)(row < n ? row : n - 1) * ld + col;
-                if constexpr (NT) {
-                    x[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(X + off));
-                    g[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(G + off));
-                } else {
-                    x[u] = *reinterpret_cast<const f32x4u *>(X + off);
-                    g[u] = *reinterpret_cast<const f32x4u *>(G + off);
-                }
+                if constexpr (NT == 1) x[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(X + off));
+                else x[u] = *reinterpret_cast<const f32x4u *>(X + off);
+                if constexpr (NT != 0) g[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(G + off));
+                else g[u] = *reinterpret_cast<const f32x4u *>(G + off);
             }
 #pragma unroll
             for (int u = 0; u < U; ++u) {

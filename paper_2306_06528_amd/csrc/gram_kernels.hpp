@@ -75,7 +75,13 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
     const int64_t nthreads = (int64_t)gridDim.x * 256;
     // two column groups per iteration when the registers allow: twice the loads in flight
     constexpr int U = (N <= 8) ? 2 : 1;
-    for (int64_t grp = (int64_t)blockIdx.x * 256 + threadIdx.x; grp < ngroups; grp += U * nthreads) {
+    // The columns are walked from the far end: the update that follows walks them from the near
+    // end, so each pass starts on the part of X that the pass before it touched last and that the
+    // memory-side cache still holds.
+    const int64_t grp0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t cnt = (grp0 < ngroups) ? (ngroups - 1 - grp0) / (U * nthreads) + 1 : 0;
+    for (int64_t k = cnt - 1; k >= 0; --k) {
+        const int64_t grp = grp0 + k * U * nthreads;
         f32x4 x[U][N];
 #pragma unroll
         for (int u = 0; u < U; ++u) {

@@ -44,6 +44,7 @@ struct svgd_ctx {
     int64_t carry_off;        // where in `partials` the carried list starts (floats): 0 or the upper half
     hipStream_t carry_stream; // the stream the carried sums were produced on
     int64_t partials_cap;     // floats available in `partials`
+    unsigned sweeps;          // in-place updates with carried sums so far: every other one walks X backwards
     int last_n; // 0 = nothing computed yet
     int last_hip_error;
     float *partials;  // [kMaxParts][P]
@@ -148,15 +149,15 @@ void launch_gram_valu(const float *X, int64_t D, int64_t ld, float *partials, in
 template <int N, bool EMIT, bool CARRY>
 void launch_update_valu(float *X, const float *G, float *PHI, float *coef, DevState *st,
                         int64_t D, int64_t ld, float eps, float *gram_out, int grid, hipStream_t s,
-                        const RowTable *rt)
+                        const RowTable *rt, const FusedArgs &ua)
 {
     if constexpr (!EMIT && !CARRY) {
         if (rt) {
-            update_valu_kernel<N, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, *rt, FusedArgs{});
+            update_valu_kernel<N, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, *rt, ua);
             return;
         }
     }
-    update_valu_kernel<N, EMIT, CARRY, false><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, NoRows{}, FusedArgs{});
+    update_valu_kernel<N, EMIT, CARRY, false><<<grid, 256, 0, s>>>(X, G, PHI, coef, st, D, ld, eps, gram_out, NoRows{}, ua);
 }
 
 template <int N>
@@ -261,6 +262,11 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
                hipStream_t s, const RowTable *rt = nullptr)
 {
     KernelTimer t(c, SVGD_KERNEL_UPDATE, s);
+    // With carried sums one update follows the other with nothing but tiny kernels in between:
+    // every other one walks X from the far end, so that it starts on what the previous one
+    // touched last (the part of X that the memory-side cache still holds).
+    FusedArgs ua{};
+    if (!EMIT && CARRY) ua.reverse = (int)(c->sweeps++ & 1u);
     if (n <= kValuMaxN) {
         const int64_t ngroups = (D + 3) / 4;
         // fewer, longer-lived workgroups when each one ends with a reduction of its pair sums
@@ -271,7 +277,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
             c->carry_nparts = grid;
             c->carry_off = 0;
         }
-#define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, ld, eps, c->partials, grid, s, rt)
+#define CALL(N) launch_update_valu<N, EMIT, CARRY>(X, G, PHI, c->coef, c->state, D, ld, eps, c->partials, grid, s, rt, ua)
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
     } else {
@@ -292,11 +298,13 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
 #define UPD(NBV, FULL)                                                                                       \
     do {                                                                                                     \
         if (!EMIT && !CARRY && rt)                                                                           \
-            update_mfma_kernel<NBV, false, FULL, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, *rt, FusedArgs{}); \
+            update_mfma_kernel<NBV, false, FULL, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, *rt, ua); \
         else if (!EMIT && aligned)                                                                           \
-            update_mfma_kernel<NBV, false, FULL, CARRY, true, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, FusedArgs{}); \
+            update_mfma_kernel<NBV, false, FULL, CARRY, true, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, ua); \
+        else if (CARRY && ua.reverse)                                                                        \
+            update_mfma_kernel<NBV, false, FULL, CARRY, false, false, false, CARRY><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, ua); \
         else                                                                                                 \
-            update_mfma_kernel<NBV, EMIT, FULL, CARRY, false, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, FusedArgs{}); \
+            update_mfma_kernel<NBV, EMIT, FULL, CARRY, false, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, ua); \
     } while (0)
         if (n == 16) UPD(1, true);
         else if (NB == 1) UPD(1, false);
@@ -342,7 +350,7 @@ int run_update_fused(svgd_ctx *c, float *X, const float *G, int n, int64_t D, in
 {
     KernelTimer t(c, SVGD_KERNEL_UPDATE, s);
     const int64_t P = (int64_t)n * (n + 1) / 2, half = (c->partials_cap / 2) & ~(int64_t)63;
-    const FusedArgs fa{c->partials + c->carry_off, c->carry_nparts, c->h_fixed};
+    const FusedArgs fa{c->partials + c->carry_off, c->carry_nparts, c->h_fixed, (int)(c->sweeps++ & 1u)};
     const int64_t out_off = c->carry_off == 0 ? half : 0;
     float *gram_out = c->partials + out_off;
     const int cap = (int)(half / P < kMaxParts ? half / P : kMaxParts); // partials that fit into a half
@@ -469,6 +477,7 @@ svgd_ctx *static_ctx(int dev, int *rc)
     c.carry_nparts = 0;
     c.carry_off = 0;
     c.carry_stream = nullptr;
+    c.sweeps = 0;
     c.last_n = 0;
     c.last_hip_error = 0;
     c.partials = reinterpret_cast<float *>(ptr);
@@ -509,6 +518,7 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
     c->carry_nparts = 0;
     c->carry_off = 0;
     c->carry_stream = nullptr;
+    c->sweeps = 0;
     c->partials_cap = 0;
     c->last_n = 0;
     c->last_hip_error = 0;
@@ -629,6 +639,7 @@ int svgd_step_ld(svgd_handle_t c, float *X, const float *G, int n, int64_t D, in
     } else {
         rc = run_kernel_matrix(c, X, n, D, ld, s, use_carry);
         if (rc) return rc;
+        if (!use_carry) c->sweeps = 0; // a Gram pass ends at the near end of X: the update starts there
         if (!carry_mode) return run_update<false, false>(c, X, G, nullptr, n, D, ld, eps, s);
         rc = run_update<false, true>(c, X, G, nullptr, n, D, ld, eps, s);
     }
@@ -761,20 +772,27 @@ int svgd_diag_copy(void *dst, const void *src, int64_t nbytes, void *stream)
 int svgd_diag_axpy_rows(float *X, const float *G, int n, int64_t D, int64_t ld, float s, int pattern,
                         int workgroups, void *stream)
 {
-    if (!X || !G || n < 1 || D < 1 || ld < D || workgroups < 1 || workgroups > 65536 || pattern < 0 || pattern > 7)
+    const int base = pattern & 15, reverse = (pattern >> 4) & 1;
+    if (!X || !G || n < 1 || D < 1 || ld < D || workgroups < 1 || workgroups > 65536 || pattern < 0 || pattern > 31 || base > 11)
         return SVGD_ERR_INVALID_ARG;
     if (overlaps(X, G, n, D, ld)) return SVGD_ERR_INVALID_ARG;
     hipStream_t st = (hipStream_t)stream;
-    switch (pattern) {
-    case 0: diag_axpy_rows_kernel<0, 8, false><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    case 1: diag_axpy_rows_kernel<1, 8, false><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    case 2: diag_axpy_rows_kernel<0, 16, false><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    case 3: diag_axpy_rows_kernel<1, 16, false><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    case 4: diag_axpy_rows_kernel<0, 8, true><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    case 5: diag_axpy_rows_kernel<1, 8, true><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    case 6: diag_axpy_rows_kernel<0, 16, true><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
-    default: diag_axpy_rows_kernel<1, 16, true><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s); break;
+#define AXPY(PAT, U, NT) diag_axpy_rows_kernel<PAT, U, NT><<<workgroups, 256, 0, st>>>(X, G, n, D, ld, s, reverse)
+    switch (base) {
+    case 0: AXPY(0, 8, 0); break;
+    case 1: AXPY(1, 8, 0); break;
+    case 2: AXPY(0, 16, 0); break;
+    case 3: AXPY(1, 16, 0); break;
+    case 4: AXPY(0, 8, 1); break;
+    case 5: AXPY(1, 8, 1); break;
+    case 6: AXPY(0, 16, 1); break;
+    case 7: AXPY(1, 16, 1); break;
+    case 8: AXPY(0, 8, 2); break;
+    case 9: AXPY(1, 8, 2); break;
+    case 10: AXPY(0, 16, 2); break;
+    default: AXPY(1, 16, 2); break;
     }
+#undef AXPY
     return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
 }
 

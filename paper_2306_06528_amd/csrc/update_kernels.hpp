@@ -29,6 +29,12 @@ struct FusedArgs {
     const float *partials_in; // [nparts_in][n (n + 1) / 2], format of the Gram kernels
     int nparts_in;
     double h_fixed;
+    // Not about fusion, but every update kernel takes this struct: walk the columns from the far
+    // end.  Which thread or wave owns which columns does not change, only the order in which it
+    // visits them.  A caller that alternates the direction from step to step starts every pass
+    // on the part of X that the previous pass touched last, i.e. on what the memory-side cache
+    // still holds.
+    int reverse;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -91,11 +97,15 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
             z[j] = load4_stream(G + (ROWS ? rt.g[ROWS ? j : 0] : (int64_t)j * ld), c, D, fl);
         }
     };
+    // this thread's groups: grp0 + k * nthreads, k < cnt, visited upwards or (reverse) downwards
     const int64_t grp0 = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t cnt = (grp0 < ngroups) ? (ngroups - 1 - grp0) / nthreads + 1 : 0;
+    const int64_t gstep = fa.reverse ? -nthreads : nthreads;
+    int64_t grp = fa.reverse ? grp0 + (cnt - 1) * nthreads : grp0;
     if constexpr (PREFETCH) {
-        if (grp0 < ngroups) load_group(grp0);
+        if (cnt > 0) load_group(grp);
     }
-    for (int64_t grp = grp0; grp < ngroups; grp += nthreads) {
+    for (int64_t k = 0; k < cnt; ++k, grp += gstep) {
         const int64_t col = grp << 2;
         const bool full = (col + 4 <= D);
         if constexpr (!PREFETCH) load_group(grp);
@@ -124,7 +134,7 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
         }
         if constexpr (CARRY) {
             if constexpr (PREFETCH) {
-                if (grp + nthreads < ngroups) load_group(grp + nthreads);
+                if (k + 1 < cnt) load_group(grp + gstep);
             }
 #pragma unroll
             for (int i = 0; i < N; ++i) {
@@ -263,7 +273,8 @@ __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 // has to mask its left edge, is a separate, branchy instance of the same code.
 // ROWS: the particles are n separately allocated rows; row addresses (and store alignments) come
 // from a RowTable instead of i * ld (plain in-place step only, re-aligned stores).
-template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false, bool ROWS = false, bool FUSED = false>
+template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false, bool ROWS = false, bool FUSED = false,
+          bool REV = false>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
                         float *__restrict__ coef, DevState *__restrict__ st, int n,
@@ -273,6 +284,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     static_assert(!FUSED || (CARRY && !ROWS && NB <= 2), "the fused step: carried pair sums, n <= 32");
     static_assert(!(CARRY && EMIT), "the Gram is carried only when X is updated");
     static_assert(!(ROWS && (EMIT || CARRY || ALIGNED)), "separate rows: plain in-place step, re-aligned stores");
+    static_assert(!REV || (CARRY && !ALIGNED && !FUSED), "the mirrored walk exists for re-aligned stores with carried sums");
     constexpr int NS = 4 * NB; // contraction steps = rows per lane
     constexpr int NPAIR = NB * (NB + 1) / 2;
     // [A operands: NB*NB*64 float4][4 waves x (cur + carry)]
@@ -368,6 +380,13 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         t1 = (t0 + per < nfull) ? t0 + per : nfull;
     }
     const int64_t c_begin = t0 << 6;
+    // visiting order: tiles t_first + k * t_step, k < ntiles.  ALIGNED kernels take the direction
+    // at run time; re-aligned stores hand a row's leftover from tile to tile, so their mirror
+    // image, which walks right to left, is an instance of its own (REV).
+    const int64_t ntiles = (t1 - t0 + TS - 1) / TS;
+    const bool rev = REV || (ALIGNED && fa.reverse != 0);
+    const int64_t t_step = rev ? -TS : TS;
+    const int64_t t_first = rev ? t0 + (ntiles - 1) * TS : t0;
 
     // lane part of every load address: row 4q, column 4c; the rest is wave-uniform
     const int64_t in_lane = ROWS ? (int64_t)(4 * c16) : (int64_t)(4 * q) * ld + 4 * c16;
@@ -443,7 +462,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         }
     };
     if (t0 < t1) {
-        int64_t in_off = in_lane + c_begin;
+        int64_t in_off = in_lane + (t_first << 6);
         opaque(in_off);
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
@@ -457,10 +476,10 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         load_next(X + in_off, G + in_off);
     }
 
-    auto process_tile = [&](auto first_tag, int64_t tile) __attribute__((always_inline)) {
+    auto process_tile = [&](auto first_tag, int64_t tile, bool last) __attribute__((always_inline)) {
         constexpr bool FIRST = decltype(first_tag)::value;
         const int64_t base = tile << 6;
-        const int64_t next = (tile + TS < t1) ? tile + TS : tile;
+        const int64_t next = last ? tile : tile + t_step;
         int64_t in_off = in_lane + (next << 6);
         int64_t out_off = out_lane + base;
         const int qv = q; // (the per-row store offsets are tile-invariant and may be hoisted)
@@ -505,30 +524,34 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             const int rloc = 4 * k + qv;         // row within the block
             const int row = urow + qv;
             const int ri = ROWS ? sri[ROWS ? row : 0] : (int)((a0 + (uint32_t)row * dm) & 31u);
-            const int o0 = 4 * c16 - ri;         // window offset relative to the tile start
+            // the row's 64-float window starts on a line boundary: ri floats before the tile, or
+            // (REV) 32 - ri floats into it, where it takes in the head of the tile to the right
+            const int sh = REV ? ((32 - ri) & 31) : -ri;
+            const int o0 = 4 * c16 + sh;         // window offset relative to the tile start
             f32x4 v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const int o = o0 + e; // one address, so nothing is read outside the arrays
-                v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : cur_index(rloc, o)];
+                if constexpr (REV) v[e] = cur[(o >= 64) ? (kUpdCur + row * 32 + o - 64) : cur_index(rloc, o)];
+                else v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : cur_index(rloc, o)];
             }
             if (FULLROWS || row < n) {
-                float *dst = ot + (ROWS ? srow[ROWS ? row : 0] : (int64_t)urow * ld) - ri;
+                float *dst = ot + (ROWS ? srow[ROWS ? row : 0] : (int64_t)urow * ld) + sh;
                 if constexpr (!FIRST) {
                     __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(dst));
-                } else { // left end of the range: nothing left of c_begin is ours
+                } else { // the end of the range the walk starts from: nothing beyond it is ours
 #pragma unroll
                     for (int e = 0; e < 4; ++e)
-                        if (o0 + e >= 0) dst[e] = v[e];
+                        if (REV ? (o0 + e < 64) : (o0 + e >= 0)) dst[e] = v[e];
                 }
             }
         };
-        // after E(b): the block's last 32 columns become the carry of its 16 rows
+        // after E(b): the block's last (REV: first) 32 columns become the carry of its 16 rows
         auto carry_copy = [&](int b) __attribute__((always_inline)) {
-            const int rloc = lane >> 2, cc = 32 + 8 * (lane & 3);
+            const int rloc = lane >> 2, cc = (REV ? 0 : 32) + 8 * (lane & 3);
             const f32x4 v0 = *reinterpret_cast<const f32x4 *>(&cur[cur_index(rloc, cc)]);
             const f32x4 v1 = *reinterpret_cast<const f32x4 *>(&cur[cur_index(rloc, cc + 4)]);
-            float *dstc = &carry[(16 * b + rloc) * 32 + (cc - 32)];
+            float *dstc = &carry[(16 * b + rloc) * 32 + (cc & 31)];
             *reinterpret_cast<f32x4 *>(dstc) = v0;
             *reinterpret_cast<f32x4 *>(dstc + 4) = v1;
         };
@@ -613,20 +636,26 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     };
 
     if constexpr (ALIGNED) { // no left edge to mask
-        for (int64_t tile = t0; tile < t1; tile += TS) process_tile(std::false_type{}, tile);
+        int64_t tile = t_first;
+        for (int64_t k = 0; k < ntiles; ++k, tile += t_step) process_tile(std::false_type{}, tile, k + 1 == ntiles);
     } else if (t0 < t1) {
-        process_tile(std::true_type{}, t0);
-        for (int64_t tile = t0 + 1; tile < t1; ++tile) process_tile(std::false_type{}, tile);
+        process_tile(std::true_type{}, t_first, ntiles == 1);
+        int64_t tile = t_first + t_step;
+        for (int64_t k = 1; k < ntiles; ++k, tile += t_step) process_tile(std::false_type{}, tile, k + 1 == ntiles);
     }
 
-    // flush: the last r_i columns of the range are still in the carry
+    // flush: the last r_i columns of the range (REV: its first 32 - r_i) are still in the carry
     if (!ALIGNED && t1 > t0) {
         const int64_t c_end = t1 << 6;
         for (int idx = lane; idx < 16 * NB * 32; idx += 64) {
             const int row = idx >> 5, cc = idx & 31;
             const int ri = ROWS ? sri[ROWS ? row : 0] : (int)((a0 + (uint32_t)row * dm) & 31u);
-            if (row < n && cc >= 32 - ri && c_end - 32 + cc >= c_begin)
-                OUT[(ROWS ? srow[ROWS ? row : 0] : (int64_t)row * ld) + c_end - 32 + cc] = carry[row * 32 + cc];
+            if constexpr (REV) {
+                if (row < n && cc < ((32 - ri) & 31)) OUT[(int64_t)row * ld + c_begin + cc] = carry[row * 32 + cc];
+            } else {
+                if (row < n && cc >= 32 - ri && c_end - 32 + cc >= c_begin)
+                    OUT[(ROWS ? srow[ROWS ? row : 0] : (int64_t)row * ld) + c_end - 32 + cc] = carry[row * 32 + cc];
+            }
         }
     }
 

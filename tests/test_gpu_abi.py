@@ -88,7 +88,7 @@ def test_profiling_selects_kernel_kinds(mod):
         assert [v[1] for v in eng.profile_end().values()] == [0, 0, 0, 0]
 
 
-@pytest.mark.parametrize("pattern", list(range(8)))
+@pytest.mark.parametrize("pattern", list(range(12)) + [16, 21, 27])
 @pytest.mark.parametrize("n,D,ld", [(64, 20_011, 20_032), (8, 70_001, 70_001), (33, 1000, 1003), (3, 63, 64)])
 def test_diag_axpy_rows(mod, pattern, n, D, ld):
     """The yardstick kernel does what it says (x += s * g on the n x D window, nothing outside)."""
@@ -101,5 +101,6 @@ def test_diag_axpy_rows(mod, pattern, n, D, ld):
     torch.cuda.synchronize()
     assert torch.allclose(buf, want, rtol=0, atol=1e-6)
     assert torch.equal(buf[:, D:], want[:, D:])
-    assert mod._lib.svgd_diag_axpy_rows(X.data_ptr(), G.data_ptr(), n, D, ld, 0.25, 8, 7, None) == -1
+    assert mod._lib.svgd_diag_axpy_rows(X.data_ptr(), G.data_ptr(), n, D, ld, 0.25, 12, 7, None) == -1
+    assert mod._lib.svgd_diag_axpy_rows(X.data_ptr(), G.data_ptr(), n, D, ld, 0.25, 32, 7, None) == -1
     assert mod._lib.svgd_diag_axpy_rows(X.data_ptr(), G.data_ptr(), n, D, ld, 0.25, 0, 0, None) == -1

@@ -474,11 +474,14 @@ def test_more_than_2_to_31_elements(svgd, n, D, carry, padded):
 @pytest.mark.parametrize("padded", [False, True])
 @pytest.mark.parametrize("n,D", [(64, 70_001), (32, 4096), (17, 1531), (48, 129), (33, 200_000), (64, 63),
                                  (8, 100_003), (4, 1024), (16, 8577), (12, 70_001), (1, 100), (2, 65),
-                                 (8, 3_000_017), (16, 70_001), (48, 20_011), (49, 5003)])
+                                 (8, 3_000_017), (16, 70_001), (48, 20_011), (49, 5003), (64, 300_007), (12, 600_001)])
 def test_carried_gram_matches_oracle_every_step(svgd, n, D, padded):
     """Four steps in a row with carried pair sums, on dense rows and on rows padded to 128 bytes
     (the layout that selects the direct-store instance of the matrix-core update kernel): h, K,
-    phi against the oracle and X_new == fl32(x + eps * phi_gpu) to one ulp, every step."""
+    phi against the oracle and X_new == fl32(x + eps * phi_gpu) to one ulp, every step.  Successive
+    carried updates walk X in alternating directions, so steps 1 and 3 are backward walks and
+    step 2 takes its h and K from the sums a backward walk left; the larger D give every
+    wave several tiles (or every thread several column groups) in both directions."""
     X, G = _random_problem(n, D, 31 * n + D, x_std=0.3)
     check_carried_chain(svgd, X, G, 0.05, padded=padded, steps=4)
 
@@ -562,13 +565,14 @@ def test_carried_gram_is_dropped_on_another_stream(svgd):
 def test_full_size_carried_gram(svgd, cfg_index, padded):
     """Full-size configs in the launch configurations the benchmark times: pair sums carried from
     the previous update, rows padded to 128 bytes (the headline; at config 5 this is the instance
-    update_mfma_kernel<4, false, true, true, true>) and dense rows.  Two steps, the second on carried
-    sums; each step: h and K against the oracle, phi of ALL columns against the oracle at 1e-4 of
-    max|phi|, X_new == fl32(x + eps * phi_gpu) to one ulp on all n * D entries."""
+    update_mfma_kernel<4, false, true, true, true>) and dense rows.  Three steps: the first after
+    a Gram pass, the second on carried sums and walking X backwards, the third on the sums that
+    backward walk left; each step: h and K against the oracle, phi of ALL columns against the
+    oracle at 1e-4 of max|phi|, X_new == fl32(x + eps * phi_gpu) to one ulp on all n * D entries."""
     wl = workloads.make(cfg_index, device="cuda")
     X0 = wl.X0
     G = wl.score(X0, 0)
-    check_carried_chain(svgd, X0, G, wl.cfg.eps, padded=padded, steps=2)
+    check_carried_chain(svgd, X0, G, wl.cfg.eps, padded=padded, steps=3)
 
 
 @pytest.mark.parametrize("n", [8, 32, 64])
