@@ -62,6 +62,10 @@ enum svgd_status {
  * by nobody else; after touching X (or to be safe) call svgd_forget_carry.  svgd_bandwidth and
  * svgd_phi always recompute from X and drop the carried sums, and so does a svgd_step on another
  * stream than the step that produced them.
+ * Successive steps on carried sums walk the columns of X in alternating directions (the new X is
+ * the same either way), so that each starts on the part of X that is still in the memory-side
+ * cache; the direction is chosen when the call is made.  A caller who captures steps into a HIP
+ * graph keeps that benefit by capturing an even number of consecutive steps per graph.
  */
 #define SVGD_FLAG_CARRY_GRAM 1u
 /*

@@ -61,7 +61,9 @@ __device__ __forceinline__ void pair_accumulate(f32x4 (&x)[N], float (&acc)[N * 
     }
 }
 
-template <int N, bool ROWS = false>
+// STREAM: loads with the streaming hint, see gram_mfma_kernel (here also for unaligned rows: a
+// wave covers 1 KiB of a row, the one line it shares with its neighbour matters little).
+template <int N, bool ROWS = false, bool STREAM = false>
 __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict__ X, int64_t D, int64_t ld,
                                                         float *__restrict__ partials,
                                                         typename RowArg<ROWS>::type rt)
@@ -88,7 +90,10 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
             const int64_t col = (grp + u * nthreads) << 2; // past the end: every load is masked to 0
             const bool full = (col + 4 <= D);
 #pragma unroll
-            for (int j = 0; j < N; ++j) x[u][j] = load4(X + (ROWS ? rt.x[ROWS ? j : 0] : (int64_t)j * ld), col, D, full);
+            for (int j = 0; j < N; ++j) {
+                const float *xr = X + (ROWS ? rt.x[ROWS ? j : 0] : (int64_t)j * ld);
+                x[u][j] = STREAM ? load4_stream(xr, col, D, full) : load4(xr, col, D, full);
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) pair_accumulate<N>(x[u], acc);
@@ -123,7 +128,13 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
 // ---------------------------------------------------------------------------------------------
 constexpr int kGramWaves = 4; // waves per workgroup; adjacent 64-column slabs -> 1 KiB per row
 
-template <int NB, bool ROWS = false>
+// STREAM: the loads carry the streaming hint (no allocation on the way in).  For rows on 128-byte
+// boundaries - nothing is shared between the slabs of neighbouring waves - and an X of more than
+// twice the memory-side cache, where little of what this pass leaves behind would be found again
+// by the update: then the pass itself runs 5 % (n = 64, D = 11.2 M) to 28 % (n = 16, same D)
+// faster.  A smaller X is loaded plainly so that the update finds it cached (with the hint, the
+// step at n = 32, D = 2,000,000 loses more in the update than the pass gains).
+template <int NB, bool ROWS = false, bool STREAM = false>
 __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float *__restrict__ X, int n,
                                                                     int64_t D, int64_t ld, float *__restrict__ partials,
                                                                     typename RowArg<ROWS>::type rt)
@@ -157,7 +168,12 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int row = 4 * i + q;
-            x[i] = (row < n) ? load4(X + (ROWS ? xro[ROWS ? i : 0] : (int64_t)row * ld), col, D, full) : f32x4{0.f, 0.f, 0.f, 0.f};
+            if (row < n) {
+                const float *xr = X + (ROWS ? xro[ROWS ? i : 0] : (int64_t)row * ld);
+                x[i] = STREAM ? load4_stream(xr, col, D, full) : load4(xr, col, D, full);
+            } else {
+                x[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
         }
     };
     if ((int64_t)blockIdx.x < ntile) load_slab(blockIdx.x);

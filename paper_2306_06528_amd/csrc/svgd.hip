@@ -23,6 +23,7 @@ namespace {
 
 constexpr uint32_t kMagic = 0x53564744u; // "SVGD"
 constexpr int kMaxParts = 2048;          // upper bound on Gram workgroups (= partial vectors)
+constexpr int64_t kMemorySideCacheBytes = (int64_t)256 << 20; // this part's memory-side cache (between L2 and HBM)
 
 } // namespace
 
@@ -138,10 +139,12 @@ bool overlaps(const float *a, const float *b, int n, int64_t D, int64_t ld)
 // rt != nullptr: the particles are separate rows (svgd_step_rows); the table goes along by value
 template <int N>
 void launch_gram_valu(const float *X, int64_t D, int64_t ld, float *partials, int grid, hipStream_t s,
-                      const RowTable *rt)
+                      const RowTable *rt, bool stream_x)
 {
     if (rt)
         gram_valu_kernel<N, true><<<grid, 256, 0, s>>>(X, D, ld, partials, *rt);
+    else if (stream_x)
+        gram_valu_kernel<N, false, true><<<grid, 256, 0, s>>>(X, D, ld, partials, NoRows{});
     else
         gram_valu_kernel<N, false><<<grid, 256, 0, s>>>(X, D, ld, partials, NoRows{});
 }
@@ -204,6 +207,8 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
     const int cap_parts = max_parts(c, n);
     int nparts, mode;
     const float *partials = c->partials; // where the list of partials for pass 2 starts
+    // streaming loads in pass 1: X well beyond what the memory-side cache could keep for the update
+    const bool big_x = !rt && (int64_t)n * ld * (int64_t)sizeof(float) > 2 * kMemorySideCacheBytes;
     if (use_carry) {
         nparts = c->carry_nparts;
         partials += c->carry_off;
@@ -212,8 +217,9 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
         const int64_t ngroups = (D + 3) / 4;
         nparts = clampi((ngroups + 255) / 256, 1, mini(c->num_cu * 3, cap_parts)); // all resident at once; each ends with a reduction
         mode = (n <= 8) ? kModeDiff : kModeGram;
+        const bool stream_x = big_x;
         KernelTimer t(c, SVGD_KERNEL_GRAM, s);
-#define CALL(N) launch_gram_valu<N>(X, D, ld, c->partials, nparts, s, rt)
+#define CALL(N) launch_gram_valu<N>(X, D, ld, c->partials, nparts, s, rt, stream_x)
         SVGD_SWITCH_N(n, CALL)
 #undef CALL
     } else {
@@ -222,9 +228,11 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
         nparts = clampi(ntile, 1, mini(c->num_cu * 2, cap_parts));
         mode = kModeGram;
         const int NB = (n + 15) / 16;
+        const bool stream_x = big_x && rows_aligned(X, ld); // slabs of unaligned rows share lines
 #define GRAM(NBV)                                                                                            \
     do {                                                                                                     \
         if (rt) gram_mfma_kernel<NBV, true><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, *rt); \
+        else if (stream_x) gram_mfma_kernel<NBV, false, true><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}); \
         else gram_mfma_kernel<NBV, false><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}); \
     } while (0)
         if (NB == 1) GRAM(1);
