@@ -242,7 +242,7 @@ int swag_update_moments(float *mean, float *sqmean, const float *X, int n, int64
 /*
  * svgd_step_ld for callers that cannot allocate: code under HIP graph capture, tight serving
  * loops, harnesses that forbid hipMalloc.  No handle: the scratch (partial sums, their reduction,
- * h, K and the coefficient tables, 4.3 MB) is a static device array inside the library, one copy
+ * h, K and the coefficient tables, 4.6 MB) is a static device array inside the library, one copy
  * per GPU, held until the process ends.  Plain step on the current device: median-heuristic
  * bandwidth, pair sums recomputed from X every call (nothing is carried), X updated in place;
  * same kernels and results as svgd_step_ld on a handle created with flags = 0.  Calls no

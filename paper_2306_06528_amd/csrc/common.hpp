@@ -78,6 +78,28 @@ __device__ inline f32x4 load4_stream(const float *__restrict__ row, int64_t col,
     return load4(row, col, D, false);
 }
 
+// How the matrix-core passes share the nfull = D / 64 full 64-column tiles among nwg worker
+// workgroups of four waves: either every wave owns a contiguous range [t0, t1) (stride 1), or the
+// workgroup owns one and its waves take every fourth tile of it, t0, t0 + 4, ... < t1 (adjacent).
+// The Gram pass and the update use the same split, so that one can start on the tiles the other
+// touched last.
+__device__ inline void tile_range(int64_t nfull, int64_t nwg, int64_t wg, int wave, bool adjacent, int64_t &t0,
+                                  int64_t &t1)
+{
+    if (adjacent) {
+        const int64_t per = (nfull + nwg - 1) / nwg;
+        const int64_t b0 = (wg * per < nfull) ? wg * per : nfull;
+        t1 = (b0 + per < nfull) ? b0 + per : nfull;
+        t0 = (b0 + wave < t1) ? b0 + wave : t1;
+    } else {
+        const int64_t nwaves = nwg * 4;
+        const int64_t per = (nfull + nwaves - 1) / nwaves;
+        const int64_t w = wg * 4 + wave;
+        t0 = (w * per < nfull) ? w * per : nfull;
+        t1 = (t0 + per < nfull) ? t0 + per : nfull;
+    }
+}
+
 // rows that all start on a 128-byte boundary
 __host__ inline bool rows_aligned(const void *base, int64_t ld)
 {

@@ -126,23 +126,42 @@ __global__ __launch_bounds__(256) void gram_valu_kernel(const float *__restrict_
 //      lane (q, c), register r of pair (b, b') holds S[16b + 4q + r][16b' + c].
 // Any assignment of columns to k-slots is valid because every column is summed exactly once.
 // ---------------------------------------------------------------------------------------------
-constexpr int kGramWaves = 4; // waves per workgroup; adjacent 64-column slabs -> 1 KiB per row
+// Order of the slabs.  The update re-reads X right after this pass, every wave (or workgroup) of it
+// walking a contiguous range of 64-column tiles from the left (tile_range).  What the memory-side
+// cache holds of X when the update starts should therefore be the first `hot` tiles of each of
+// those `nranges` ranges of `per` tiles, and this pass visits them last: its index space is
+//     [0, I1)        the other ("cold") tiles, range after range,
+//     [I1, I1 + I2)  the hot tiles, range after range,
+//     I1 + I2        the partial slab after the last full tile, if D mod 64 != 0,
+// with I1 = nranges * (per - hot), I2 = nranges * hot (indices that fall beyond a short last range
+// are empty slabs), and wave w of workgroup b takes the indices 4 (b + k * gridDim.x) + w: the
+// workgroups sweep the index space together, the four waves of one on adjacent slabs.
+constexpr int kGramWaves = 4; // waves per workgroup, as in the update kernel
 
-// STREAM: the loads carry the streaming hint (no allocation on the way in).  For rows on 128-byte
-// boundaries - nothing is shared between the slabs of neighbouring waves - and an X of more than
-// twice the memory-side cache, where little of what this pass leaves behind would be found again
-// by the update: then the pass itself runs 5 % (n = 64, D = 11.2 M) to 28 % (n = 16, same D)
-// faster.  A smaller X is loaded plainly so that the update finds it cached (with the hint, the
-// step at n = 32, D = 2,000,000 loses more in the update than the pass gains).
-template <int NB, bool ROWS = false, bool STREAM = false>
+// (a wave's indices are `stride` = 4 * gridDim.x apart; its quotient and remainder by the lengths
+// of a range's cold and hot parts come from the host, so that stepping from one index to the next
+// needs no division; everything fits 32 bits, the host sees to that)
+struct GramOrder {
+    uint32_t nranges, per, hot;
+    uint32_t q_cold, r_cold; // stride = q_cold * (per - hot) + r_cold   (0, 0 if per == hot)
+    uint32_t q_hot, r_hot;   // stride = q_hot * hot + r_hot             (0, 0 if hot == 0)
+};
+
+// ORDER 0: plain order, index = tile (go is not looked at) - for an X that the memory-side cache
+//   holds anyway, or nearly: there the bookkeeping of the order costs more than the order gains.
+// ORDER 1: the order described above.
+// ORDER 2: the same, and the cold tiles are loaded with the streaming hint (no allocation on the
+//   way in) - for rows on 128-byte boundaries (nothing is shared between the slabs of neighbouring
+//   waves).  The pass itself then runs 5 % (n = 64, D = 11.2 M) to 28 % (n = 16, same D) faster.
+// The host takes ORDER 1 or 2 when X is larger than twice the memory-side cache.
+template <int NB, bool ROWS = false, int ORDER = 0>
 __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float *__restrict__ X, int n,
                                                                     int64_t D, int64_t ld, float *__restrict__ partials,
-                                                                    typename RowArg<ROWS>::type rt)
+                                                                    typename RowArg<ROWS>::type rt, GramOrder go)
 {
     constexpr int NROW = 16 * NB;
     constexpr int RPL = 4 * NB; // rows per lane while loading
     constexpr int NPAIR = NB * (NB + 1) / 2;
-    constexpr int TW = 64 * kGramWaves; // columns per workgroup tile
     __shared__ float lds[kGramWaves][NROW * 64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -154,30 +173,76 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
 #pragma unroll
     for (int p = 0; p < NPAIR; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int64_t ntile = (D + TW - 1) / TW;
+    static_assert(!(ROWS && ORDER != 0), "separate rows: plain order");
+    constexpr bool ORDERED = ORDER != 0, STREAM = ORDER == 2;
+    const int64_t nfull = D >> 6;
+    const uint32_t uper = go.per, uhot = go.hot, ucold = uper - uhot, unfull = (uint32_t)nfull;
+    const uint32_t I1 = ORDERED ? go.nranges * ucold : 0u, I2 = ORDERED ? go.nranges * uhot : unfull;
+    const uint32_t nidx = I1 + I2 + (((nfull << 6) < D) ? 1u : 0u);
+    const uint32_t lo = 4u * blockIdx.x + (uint32_t)__builtin_amdgcn_readfirstlane(wave), stride = 4u * gridDim.x;
+    // the walk: index `at` is tile r * per + o (+ hot while cold), or the partial slab (phase 2)
+    uint32_t at = lo, phase = 0, r = 0, o = 0;
+    auto enter = [&]() { // state at index `at`, by division: once per wave and phase
+        if (at < I1) {
+            phase = 0;
+            r = at / ucold;
+            o = at - r * ucold;
+        } else if (at < I1 + I2) {
+            phase = 1;
+            r = (at - I1) / uhot;
+            o = (at - I1) - r * uhot;
+        } else {
+            phase = 2;
+        }
+    };
+    auto advance = [&]() {
+        at += stride;
+        if constexpr (ORDERED) {
+            if (phase == 0 && at < I1) {
+                o += go.r_cold;
+                r += go.q_cold;
+                if (o >= ucold) { o -= ucold; ++r; }
+            } else if (phase == 1 && at < I1 + I2) {
+                o += go.r_hot;
+                r += go.q_hot;
+                if (o >= uhot) { o -= uhot; ++r; }
+            } else if (phase < 2) {
+                enter();
+            }
+        }
+    };
+    if constexpr (ORDERED) enter();
     f32x4 x[RPL];
     int64_t xro[ROWS ? RPL : 1]; // where this lane's rows start (separate rows only)
     if constexpr (ROWS) {
 #pragma unroll
         for (int i = 0; i < RPL; ++i) xro[i] = (4 * i + q < n) ? rt.x[ROWS ? 4 * i + q : 0] : 0;
     }
-    auto load_slab = [&](int64_t tile) {
-        const int64_t wcol = tile * TW + (wave << 6);
+    auto load_slab = [&]() __attribute__((always_inline)) { // the slab at `at`; then on to the next index
+        const bool is_cold = ORDERED && phase == 0;
+        int64_t tile = ORDERED ? nfull : (int64_t)at; // ordered, phase 2: the partial slab
+        if (ORDERED && phase < 2) {
+            const uint32_t t = r * uper + (is_cold ? uhot : 0u) + o;
+            const uint32_t end = ((uint64_t)(r + 1) * uper < unfull) ? (r + 1) * uper : unfull;
+            tile = t < end ? (int64_t)t : -1; // beyond a short last range: an empty slab
+        }
+        advance();
+        const int64_t wcol = tile << 6;
         const int64_t col = wcol + 4 * c16;
         const bool full = (wcol + 64 <= D);
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int row = 4 * i + q;
-            if (row < n) {
+            if ((!ORDERED || tile >= 0) && row < n) {
                 const float *xr = X + (ROWS ? xro[ROWS ? i : 0] : (int64_t)row * ld);
-                x[i] = STREAM ? load4_stream(xr, col, D, full) : load4(xr, col, D, full);
+                x[i] = (STREAM && is_cold) ? load4_stream(xr, col, D, full) : load4(xr, col, D, full);
             } else {
-                x[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+                x[i] = f32x4{0.f, 0.f, 0.f, 0.f}; // an empty slab adds nothing to any sum
             }
         }
     };
-    if ((int64_t)blockIdx.x < ntile) load_slab(blockIdx.x);
-    for (int64_t tile = blockIdx.x; tile < ntile; tile += gridDim.x) {
+    if (lo < nidx) load_slab();
+    for (uint32_t idx = lo; idx < nidx; idx += stride) {
         f32x4 s = x[0];
 #pragma unroll
         for (int i = 1; i < RPL; ++i) s += x[i];
@@ -197,7 +262,7 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
             *reinterpret_cast<f32x4 *>(&my[row * 64 + ((c16 ^ (row & 15)) << 2)]) = x[i] - s;
         }
         // the next slab's loads are in flight while this one is multiplied
-        if (tile + gridDim.x < ntile) load_slab(tile + gridDim.x);
+        if (idx + stride < nidx) load_slab();
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             f32x4 a[NB];

@@ -198,10 +198,29 @@ int max_parts(const svgd_ctx *c, int n)
     return (int)(m < kMaxParts ? m : kMaxParts);
 }
 
+// Whether the matrix-core update on aligned rows lets the waves of a workgroup share a range.
+bool adjacent_tiles(int n, int64_t ld)
+{
+    return n > 48 || (int64_t)n * ld * (int64_t)sizeof(float) > kMemorySideCacheBytes + kMemorySideCacheBytes / 4;
+}
+
+// Worker workgroups of the matrix-core update (each walks ranges of 64-column tiles; one more
+// workgroup does D mod 64): one per CU - the kernel overlaps its own loads with its multiplies, and
+// fewer concurrent row streams keep more HBM pages open.  The Gram pass splits the tiles the same way.
+int update_workers(const svgd_ctx *c, int n, int64_t D, bool carry)
+{
+    const int64_t nfull = D / 64;
+    const int max_workers = mini(c->num_cu, (carry ? max_parts(c, n) : kMaxParts) - 1);
+    return clampi((nfull + 3) / 4, 1, max_workers);
+}
+
 // Passes 1 and 2: Gram partials -> fp64 reduction -> h, K, coefficient tables (all on `s`).
 // With use_carry the partials the previous update left in c->partials stand in for pass 1.
+// G_next: where the in-place update that follows this call will read its scores (null: none, or
+// an update that writes phi elsewhere); carry_next: that update will carry pair sums.  Both only
+// steer the order in which pass 1 visits X.
 int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld, hipStream_t s, bool use_carry,
-                      const RowTable *rt = nullptr)
+                      const RowTable *rt = nullptr, const float *G_next = nullptr, bool carry_next = false)
 {
     const int P = n * (n + 1) / 2;
     const int cap_parts = max_parts(c, n);
@@ -224,16 +243,36 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
 #undef CALL
     } else {
         KernelTimer t(c, SVGD_KERNEL_GRAM, s);
-        const int64_t ntile = (D + 64 * kGramWaves - 1) / (64 * kGramWaves);
-        nparts = clampi(ntile, 1, mini(c->num_cu * 2, cap_parts));
         mode = kModeGram;
         const int NB = (n + 15) / 16;
+        const int64_t nfull = D / 64;
+        nparts = clampi((D + 255) / 256, 1, mini(c->num_cu * 2, cap_parts));
+        // the ranges of the update that follows (tile_range) and how many of each range's first
+        // tiles three quarters of the memory-side cache can hold
+        const bool aligned_next = G_next && !rt && rows_aligned(X, ld) && rows_aligned(G_next, ld);
+        const bool shared_ranges = aligned_next && adjacent_tiles(n, ld);
+        int64_t nranges = (int64_t)update_workers(c, n, D, carry_next) * (shared_ranges ? 1 : 4);
+        int64_t per = (nfull + nranges - 1) / nranges > 0 ? (nfull + nranges - 1) / nranges : 1;
+        int64_t hot = (3 * kMemorySideCacheBytes / 4) / ((int64_t)n * 256) / nranges;
+        if (shared_ranges) hot &= ~(int64_t)3; // four waves share the start of a range
+        if (hot > per) hot = per;
+        if (per * nranges >= ((int64_t)1 << 31) - 1) { // the kernel maps 32-bit indices: one range, nothing kept
+            nranges = 1;
+            per = nfull > 0 ? nfull : 1;
+            hot = 0;
+        }
         const bool stream_x = big_x && rows_aligned(X, ld); // slabs of unaligned rows share lines
+        const uint32_t stride = 4u * (uint32_t)nparts, cold = (uint32_t)(per - hot);
+        GramOrder go{(uint32_t)nranges, (uint32_t)per, (uint32_t)hot, 0, 0, 0, 0};
+        if (cold) { go.q_cold = stride / cold; go.r_cold = stride % cold; }
+        if (hot) { go.q_hot = stride / (uint32_t)hot; go.r_hot = stride % (uint32_t)hot; }
+        // (the order is only worth its bookkeeping for an X well beyond the memory-side cache)
 #define GRAM(NBV)                                                                                            \
     do {                                                                                                     \
-        if (rt) gram_mfma_kernel<NBV, true><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, *rt); \
-        else if (stream_x) gram_mfma_kernel<NBV, false, true><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}); \
-        else gram_mfma_kernel<NBV, false><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}); \
+        if (rt) gram_mfma_kernel<NBV, true, 0><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, *rt, go); \
+        else if (stream_x) gram_mfma_kernel<NBV, false, 2><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}, go); \
+        else if (big_x) gram_mfma_kernel<NBV, false, 1><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}, go); \
+        else gram_mfma_kernel<NBV, false, 0><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}, go); \
     } while (0)
         if (NB == 1) GRAM(1);
         else if (NB == 2) GRAM(2);
@@ -275,6 +314,9 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
     // touched last (the part of X that the memory-side cache still holds).
     FusedArgs ua{};
     if (!EMIT && CARRY) ua.reverse = (int)(c->sweeps++ & 1u);
+    // the four waves of a workgroup on adjacent tiles: always at n > 48; below only for an X beyond
+    // the memory-side cache (n = 32, D = 2,000,000, which just fits it, ran 3 % slower that way)
+    ua.adjacent = adjacent_tiles(n, ld);
     if (n <= kValuMaxN) {
         const int64_t ngroups = (D + 3) / 4;
         // fewer, longer-lived workgroups when each one ends with a reduction of its pair sums
@@ -290,11 +332,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
 #undef CALL
     } else {
         // workers walk contiguous ranges of full 64-column tiles; one more workgroup does D mod 64
-        const int64_t nfull = D / 64;
-        // one worker workgroup per CU: the kernel overlaps its own loads with its multiplies, and
-        // fewer concurrent row streams keep more HBM pages open
-        const int max_workers = mini(c->num_cu, (CARRY ? max_parts(c, n) : kMaxParts) - 1);
-        const int grid = clampi((nfull + 3) / 4, 1, max_workers) + 1;
+        const int grid = update_workers(c, n, D, CARRY) + 1;
         const int NB = (n + 15) / 16;
         if (CARRY) { // one partial per workgroup, the tail's included
             c->carry_nparts = grid;
@@ -358,7 +396,7 @@ int run_update_fused(svgd_ctx *c, float *X, const float *G, int n, int64_t D, in
 {
     KernelTimer t(c, SVGD_KERNEL_UPDATE, s);
     const int64_t P = (int64_t)n * (n + 1) / 2, half = (c->partials_cap / 2) & ~(int64_t)63;
-    const FusedArgs fa{c->partials + c->carry_off, c->carry_nparts, c->h_fixed, (int)(c->sweeps++ & 1u)};
+    const FusedArgs fa{c->partials + c->carry_off, c->carry_nparts, c->h_fixed, (int)(c->sweeps++ & 1u), 0};
     const int64_t out_off = c->carry_off == 0 ? half : 0;
     float *gram_out = c->partials + out_off;
     const int cap = (int)(half / P < kMaxParts ? half / P : kMaxParts); // partials that fit into a half
@@ -427,7 +465,7 @@ int run_tiny(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t D
 // The entry point that allocates nothing: its scratch is a file-scope device array, one copy per
 // GPU, resolved to a device address once per device.
 // ---------------------------------------------------------------------------------------------
-constexpr int kStaticMaxParts = 512;                         // partial vectors of n(n+1)/2 <= 2080 floats
+constexpr int kStaticMaxParts = 528;                         // partial vectors of n(n+1)/2 <= 2080 floats: 2 * 256 + 1 fit
 constexpr size_t kStaticPartialsBytes = (size_t)kStaticMaxParts * kMaxPairsFull * sizeof(float);
 constexpr size_t kStaticPart2Bytes = (size_t)kSlices * kMaxPairsFull * sizeof(double);
 constexpr size_t kStaticCoefBytes = (size_t)kCoefFloats * sizeof(float);
@@ -475,7 +513,7 @@ svgd_ctx *static_ctx(int dev, int *rc)
     c.device = dev;
     c.max_n = SVGD_MAX_PARTICLES;
     c.max_D = SVGD_STATIC_MAX_D;
-    c.num_cu = cus > 256 ? 256 : cus; // keeps the Gram grid (2 workgroups per CU) within kStaticMaxParts
+    c.num_cu = cus > 256 ? 256 : cus; // keeps the Gram grid (2 workgroups per CU, one for the tail) within kStaticMaxParts
     c.flags = 0;
     c.h_fixed = 0.0;
     c.carry_valid = false;
@@ -645,7 +683,7 @@ int svgd_step_ld(svgd_handle_t c, float *X, const float *G, int n, int64_t D, in
     if (use_carry && can_fuse(c, n)) {
         rc = run_update_fused(c, X, G, n, D, ld, eps, s); // the whole step in one launch
     } else {
-        rc = run_kernel_matrix(c, X, n, D, ld, s, use_carry);
+        rc = run_kernel_matrix(c, X, n, D, ld, s, use_carry, nullptr, G, carry_mode);
         if (rc) return rc;
         if (!use_carry) c->sweeps = 0; // a Gram pass ends at the near end of X: the update starts there
         if (!carry_mode) return run_update<false, false>(c, X, G, nullptr, n, D, ld, eps, s);
@@ -747,7 +785,7 @@ int svgd_step_static(float *X, const float *G, int n, int64_t D, int64_t ld, flo
     // the coefficient tables by the passes after it): nothing has to start at zero.
     hipStream_t s = (hipStream_t)stream;
     if (is_tiny(n, D)) return run_tiny<kTinyStep>(c, X, G, nullptr, n, D, ld, eps, s);
-    rc = run_kernel_matrix(c, X, n, D, ld, s, false);
+    rc = run_kernel_matrix(c, X, n, D, ld, s, false, nullptr, G, false);
     if (rc) return rc;
     return run_update<false, false>(c, X, G, nullptr, n, D, ld, eps, s);
 }

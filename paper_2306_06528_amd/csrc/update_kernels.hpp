@@ -35,6 +35,9 @@ struct FusedArgs {
     // on the part of X that the previous pass touched last, i.e. on what the memory-side cache
     // still holds.
     int reverse;
+    // ALIGNED matrix-core kernels: the four waves of a workgroup take adjacent tiles of one range
+    // instead of a range each (see tile_range).
+    int adjacent;
 };
 
 // ---------------------------------------------------------------------------------------------
@@ -360,25 +363,12 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
 
     // The tiles of this wave: t0, t0 + TS, ... < t1.  Re-aligned stores hand a row's tail from one
     // tile to the next through the wave's carry, so there each wave walks a contiguous range of
-    // its own (TS = 1).  ALIGNED has nothing to hand over: at n > 48 the workgroup owns a
-    // contiguous range and its four waves take adjacent tiles (TS = 4), which makes the
-    // workgroup's accesses 1 KiB contiguous per row (0.5-1 % faster at n = 64; at n = 32, where the
-    // working set is close to the memory-side cache, it measured 3 % slower and is not used).
-    constexpr int64_t TS = (ALIGNED && NB == 4) ? 4 : 1;
+    // its own (TS = 1).  ALIGNED has nothing to hand over: on request (fa.adjacent, the host's
+    // choice) the workgroup owns a contiguous range and its four waves take adjacent tiles
+    // (TS = 4), which makes the workgroup's accesses 1 KiB contiguous per row.
+    const int64_t TS = (ALIGNED && fa.adjacent != 0) ? 4 : 1;
     int64_t t0, t1;
-    if constexpr (TS == 4) {
-        const int64_t nwg = gridDim.x - 1;
-        const int64_t per = (nfull + nwg - 1) / nwg;
-        const int64_t b0 = ((int64_t)blockIdx.x * per < nfull) ? (int64_t)blockIdx.x * per : nfull;
-        t1 = (b0 + per < nfull) ? b0 + per : nfull;
-        t0 = (b0 + wave < t1) ? b0 + wave : t1;
-    } else {
-        const int64_t nwaves = (int64_t)(gridDim.x - 1) * 4;
-        const int64_t per = (nfull + nwaves - 1) / nwaves;
-        const int64_t w = (int64_t)blockIdx.x * 4 + wave;
-        t0 = (w * per < nfull) ? w * per : nfull;
-        t1 = (t0 + per < nfull) ? t0 + per : nfull;
-    }
+    tile_range(nfull, gridDim.x - 1, blockIdx.x, wave, TS == 4, t0, t1);
     const int64_t c_begin = t0 << 6;
     // visiting order: tiles t_first + k * t_step, k < ntiles.  ALIGNED kernels take the direction
     // at run time; re-aligned stores hand a row's leftover from tile to tile, so their mirror
