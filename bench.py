@@ -25,21 +25,21 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
     # (config, carried Gram?, rows padded to 32 floats?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True, True): (2801885.9, 2795580.1),
-    (5, False, True): (2801503.4, 2793492.0),
-    (5, True, False): (4076165.6, 2797113.2),   # mean of the two walking directions (separate instances)
-    (5, False, False): (4069508.5, 2795026.1),
-    (3, True, True): (253535.4, 250530.2),      # D = 2,000,000 is a multiple of 32: ld = D either way
-    (3, False, True): (253575.7, 250000.0),
-    (3, True, False): (253530.0, 250530.2),
-    (3, False, False): (253584.8, 250000.0),
-    (4, True, True): (353613.2, 350805.3),
-    (4, False, True): (360174.7, 352872.4),
-    (4, True, False): (369372.5, 357043.2),
-    (4, False, False): (365519.2, 355092.7),
+    (5, True, True): (2801900.4, 2795580.1),
+    (5, False, True): (2801525.4, 2793492.0),
+    (5, True, False): (4074711.0, 2797113.1),   # mean of the two walking directions (separate instances)
+    (5, False, False): (4069961.3, 2795026.1),
+    (3, True, True): (253548.2, 250530.1),      # D = 2,000,000 is a multiple of 32: ld = D either way
+    (3, False, True): (253567.1, 250000.0),
+    (3, True, False): (253553.2, 250530.1),
+    (3, False, False): (253558.8, 250000.0),
+    (4, True, True): (353613.3, 350794.3),
+    (4, False, True): (360164.2, 352875.0),
+    (4, True, False): (369274.8, 357003.1),
+    (4, False, False): (365541.7, 355103.8),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "717d19d039ea35829a65774812bd7d929131d4db4581b28eaa6b141c8f31beaa"
+TRAFFIC_SOURCE_SHA256 = "1614475ba3fa9b58990be208f650c156bfcf9e37cebb78b11a20035d8cab6088"
 
 
 def kernel_source_hash():
