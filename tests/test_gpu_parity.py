@@ -313,29 +313,36 @@ def test_config2_pinn_mlp_trajectory(svgd):
                     assert drift <= 1e-4, f"free-running drift after 100 steps {drift:.3e}"
 
 
-def _full_size_check(svgd, cfg_index):
-    """Full-size config, dense rows, plain handle (the four-kernel step of the four-call ABI): h and
-    K against the oracle's full d2, phi on ALL columns against the oracle (streamed in chunks, the
-    normaliser is the oracle's max|phi|), and the in-place update == fl32(x + eps * phi_gpu) to one
-    ulp on all n * D entries."""
-    wl = workloads.make(cfg_index, device="cuda")
-    n, D = wl.n, wl.D
-    X = wl.X0.clone()
-    G = wl.score(X, 0)
-    PHI = torch.empty_like(X)
+def _plain_step_check(svgd, X0, G, eps, padded=False):
+    """One step of a plain handle (the four-kernel step of the four-call ABI) on dense rows or on
+    rows padded to 128 bytes: h and K against the oracle's full d2, phi on ALL columns against the
+    oracle (streamed in chunks, the normaliser is the oracle's max|phi|), and the in-place update
+    == fl32(x + eps * phi_gpu) to one ulp on all n * D entries."""
+    n, D = X0.shape
+    if padded:
+        X, Gv = padded_copy(svgd, X0), padded_copy(svgd, G)
+        PHI = svgd.padded_rows(n, D, device=X0.device, fill=float("nan"))
+    else:
+        X, Gv, PHI = X0.clone(), G, torch.empty_like(X0)
     with svgd.Svgd(n, D) as eng:
-        eng.phi(X, G, PHI)
+        eng.phi(X, Gv, PHI)
         h, K = eng.get_last(n)
-        eng.step(X, G, wl.cfg.eps)
+        eng.step(X, Gv, eps)
         torch.cuda.synchronize()
-    Xh, Gh = wl.X0.cpu().numpy(), G.cpu().numpy()
+    Xh, Gh = X0.cpu().numpy(), G.cpu().numpy()
     h_ref, K_ref = oracle_kernel_matrix(Xh)
     assert abs(h - h_ref) / h_ref <= TOL_H, f"h {h} vs {h_ref}"
     assert np.abs(K - K_ref).max() <= TOL_K
     e_phi = phi_error_all_columns(PHI, Xh, Gh, K_ref, h_ref)
     assert e_phi <= TOL_PHI, f"phi err / max|phi| = {e_phi:.3e}"
-    ulps = ulp_diff_device(X, wl.X0, PHI, wl.cfg.eps)
+    ulps = ulp_diff_device(X, X0, PHI, eps)
     assert ulps <= 1.0, f"in-place update differs from x + eps*phi_gpu by {ulps} ulp"
+
+
+def _full_size_check(svgd, cfg_index):
+    """Full-size config, dense rows, plain handle."""
+    wl = workloads.make(cfg_index, device="cuda")
+    _plain_step_check(svgd, wl.X0, wl.score(wl.X0, 0), wl.cfg.eps)
 
 
 def test_config3_operator_net_full_size(svgd):
@@ -573,6 +580,19 @@ def test_full_size_carried_gram(svgd, cfg_index, padded):
     X0 = wl.X0
     G = wl.score(X0, 0)
     check_carried_chain(svgd, X0, G, wl.cfg.eps, padded=padded, steps=3)
+
+
+@pytest.mark.parametrize("padded", [True, False])
+@pytest.mark.parametrize("n,D", [(16, 9_000_001), (32, 4_400_003), (48, 3_000_001), (12, 12_000_001)])
+def test_x_beyond_the_memory_side_cache(svgd, n, D, padded):
+    """X of 550-580 MB at particle counts below 64: the sizes at which the pairwise-d2 pass visits
+    the update's first tiles last (and streams the rest, on padded rows) and at which the workgroups
+    of the matrix-core update on padded rows share a range.  The plain step, then three steps on
+    carried sums (forward, backward, forward), each checked completely against the oracle."""
+    X0, G = _random_problem(n, D, 17 * n + 3, x_std=0.05)
+    G *= 1e-2
+    _plain_step_check(svgd, X0, G, 1e-3, padded=padded)
+    check_carried_chain(svgd, X0, G, 1e-3, padded=padded, steps=3)
 
 
 @pytest.mark.parametrize("n", [8, 32, 64])
