@@ -198,19 +198,32 @@ int max_parts(const svgd_ctx *c, int n)
     return (int)(m < kMaxParts ? m : kMaxParts);
 }
 
-// Whether the matrix-core update on aligned rows lets the waves of a workgroup share a range.
-bool adjacent_tiles(int n, int64_t ld)
+// An X that the memory-side cache cannot hold (with a margin: n = 32, D = 2,000,000 just fits and
+// behaves like a cached problem).
+bool beyond_cache(int n, int64_t ld)
 {
-    return n > 48 || (int64_t)n * ld * (int64_t)sizeof(float) > kMemorySideCacheBytes + kMemorySideCacheBytes / 4;
+    return (int64_t)n * ld * (int64_t)sizeof(float) > kMemorySideCacheBytes + kMemorySideCacheBytes / 4;
 }
+
+// Whether the matrix-core update on aligned rows lets the waves of a workgroup share a range.
+bool adjacent_tiles(int n, int64_t ld) { return n > 48 || beyond_cache(n, ld); }
 
 // Worker workgroups of the matrix-core update (each walks ranges of 64-column tiles; one more
 // workgroup does D mod 64): one per CU - the kernel overlaps its own loads with its multiplies, and
-// fewer concurrent row streams keep more HBM pages open.  The Gram pass splits the tiles the same way.
-int update_workers(const svgd_ctx *c, int n, int64_t D, bool carry)
+// fewer concurrent row streams keep more HBM pages open.  Exception: particle counts just above
+// 16, whose tiles cost the instructions of 32 rows but move little more than half the bytes, so
+// that the fixed costs of a tile show.  The kernel instances for n not a multiple of 16, n < 32,
+// are built for two waves per SIMD, and for 17 <= n <= 24 and an X beyond the memory-side cache
+// two workgroups per CU overlap one's arithmetic with the other's loads (with carried sums at
+// D = 5,000,000: n = 17 225 -> 190 us, n = 24 258 -> 241 us; from n = 25 on the gain is below the
+// cost of the longer list of partial sums, with 16 or 32 particles the second workgroup costs
+// 2-5 %, and for an X that cache serves it costs 9 %).
+// The Gram pass splits the tiles the same way.
+int update_workers(const svgd_ctx *c, int n, int64_t D, int64_t ld, bool carry)
 {
     const int64_t nfull = D / 64;
-    const int max_workers = mini(c->num_cu, (carry ? max_parts(c, n) : kMaxParts) - 1);
+    const int per_cu = (n >= 17 && n <= 24 && beyond_cache(n, ld)) ? 2 : 1;
+    const int max_workers = mini(c->num_cu * per_cu, (carry ? max_parts(c, n) : kMaxParts) - 1);
     return clampi((nfull + 3) / 4, 1, max_workers);
 }
 
@@ -251,7 +264,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
         // tiles three quarters of the memory-side cache can hold
         const bool aligned_next = G_next && !rt && rows_aligned(X, ld) && rows_aligned(G_next, ld);
         const bool shared_ranges = aligned_next && adjacent_tiles(n, ld);
-        int64_t nranges = (int64_t)update_workers(c, n, D, carry_next) * (shared_ranges ? 1 : 4);
+        int64_t nranges = (int64_t)update_workers(c, n, D, ld, carry_next) * (shared_ranges ? 1 : 4);
         int64_t per = (nfull + nranges - 1) / nranges > 0 ? (nfull + nranges - 1) / nranges : 1;
         int64_t hot = (3 * kMemorySideCacheBytes / 4) / ((int64_t)n * 256) / nranges;
         if (shared_ranges) hot &= ~(int64_t)3; // four waves share the start of a range
@@ -332,7 +345,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
 #undef CALL
     } else {
         // workers walk contiguous ranges of full 64-column tiles; one more workgroup does D mod 64
-        const int grid = update_workers(c, n, D, CARRY) + 1;
+        const int grid = update_workers(c, n, D, ld, CARRY) + 1;
         const int NB = (n + 15) / 16;
         if (CARRY) { // one partial per workgroup, the tail's included
             c->carry_nparts = grid;

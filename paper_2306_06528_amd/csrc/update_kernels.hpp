@@ -278,7 +278,8 @@ __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 // from a RowTable instead of i * ld (plain in-place step only, re-aligned stores).
 template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false, bool ROWS = false, bool FUSED = false,
           bool REV = false>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+__global__ __launch_bounds__(256)
+__attribute__((amdgpu_waves_per_eu((NB <= 2 && !FULLROWS) ? 2 : 1, (NB <= 2 && !FULLROWS) ? 2 : 1)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
                         float *__restrict__ coef, DevState *__restrict__ st, int n,
                         int64_t D, int64_t ld, float eps, float *__restrict__ gram_out,

@@ -583,11 +583,13 @@ def test_full_size_carried_gram(svgd, cfg_index, padded):
 
 
 @pytest.mark.parametrize("padded", [True, False])
-@pytest.mark.parametrize("n,D", [(16, 9_000_001), (32, 4_400_003), (48, 3_000_001), (12, 12_000_001)])
+@pytest.mark.parametrize("n,D", [(16, 9_000_001), (32, 4_400_003), (48, 3_000_001), (12, 12_000_001),
+                                 (17, 5_000_003), (22, 4_000_001)])
 def test_x_beyond_the_memory_side_cache(svgd, n, D, padded):
     """X of 550-580 MB at particle counts below 64: the sizes at which the pairwise-d2 pass visits
     the update's first tiles last (and streams the rest, on padded rows) and at which the workgroups
-    of the matrix-core update on padded rows share a range.  The plain step, then three steps on
+    of the matrix-core update on padded rows share a range; X of 340-350 MB at 17 and 22 particles:
+    the sizes at which that update runs two workgroups per CU.  The plain step, then three steps on
     carried sums (forward, backward, forward), each checked completely against the oracle."""
     X0, G = _random_problem(n, D, 17 * n + 3, x_std=0.05)
     G *= 1e-2
