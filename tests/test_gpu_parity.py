@@ -597,6 +597,20 @@ def test_x_beyond_the_memory_side_cache(svgd, n, D, padded):
     check_carried_chain(svgd, X0, G, 1e-3, padded=padded, steps=3)
 
 
+@pytest.mark.parametrize("seed", list(range(48)))
+def test_random_shapes(svgd, seed):
+    """Seeded random particle counts, lengths (log-uniform up to 400,000) and layouts: a plain step
+    and three steps on carried sums, each checked completely against the oracle."""
+    rng = np.random.default_rng(1000 + seed)
+    n = int(rng.integers(1, 65))
+    D = int(np.exp(rng.uniform(0.0, np.log(400_000.0))))
+    padded = bool(rng.integers(0, 2))
+    X0, G = _random_problem(n, D, 7 * seed + 1, x_std=float(rng.choice([0.02, 0.3, 1.0])))
+    eps = float(rng.choice([1e-3, 0.05]))
+    _plain_step_check(svgd, X0, G, eps, padded=padded)
+    check_carried_chain(svgd, X0, G, eps, padded=padded, steps=3)
+
+
 @pytest.mark.parametrize("n", [8, 32, 64])
 @pytest.mark.parametrize("shift", [1, 3, 17])
 def test_buffers_with_odd_base_alignment(svgd, n, shift):
