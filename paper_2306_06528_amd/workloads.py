@@ -106,5 +106,5 @@ class Workload:
 
 
 def make(index: int, device="cpu", n: Optional[int] = None, D: Optional[int] = None) -> Workload:
-    """Workload for BASELINE config `index` (1..5); n/D override the size (distributions kept)."""
+    """Workload for benchmark configuration `index` (1..5); n/D override the size (distributions kept)."""
     return Workload(CONFIGS[index], device=device, n=n, D=D)
