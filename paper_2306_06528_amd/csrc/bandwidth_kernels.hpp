@@ -130,7 +130,17 @@ __device__ inline void minmax_to_lds(double mn, double mx, unsigned long long *s
 // whole list would wait for one LDS round trip after the other); the partial ranks meet in
 // `counters`, which must be zero on entry.  list_visible: a barrier already lies between the
 // writes of the list and this call.
-template <int THREADS>
+// Workgroup barrier.  LO ("LDS only"): for code whose barriers order nothing but LDS traffic -
+// it waits for this wave's LDS operations and not for its outstanding global loads, which
+// __syncthreads() would (the fused step has its first tile's loads in flight during pass 2).
+template <bool LO>
+__device__ inline void block_sync()
+{
+    if constexpr (LO) asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else __syncthreads();
+}
+
+template <int THREADS, bool LO = false>
 __device__ inline void rank_directly(const double *list, int len, int below, int r_lo, int r_hi, double *sel,
                                      unsigned *counters, bool list_visible)
 {
@@ -139,7 +149,7 @@ __device__ inline void rank_directly(const double *list, int len, int below, int
     static_assert(PARTS >= 1 && PARTS * kSelDirect == THREADS, "THREADS is a multiple of kSelDirect");
     const int tid = threadIdx.x;
     const int e = tid % kSelDirect, part = tid / kSelDirect;
-    if (!list_visible) __syncthreads();
+    if (!list_visible) block_sync<LO>();
     double v = 0.0;
     if (e < len) {
         v = list[e];
@@ -155,7 +165,7 @@ __device__ inline void rank_directly(const double *list, int len, int below, int
         }
         if (cnt) atomicAdd(&counters[e], cnt);
     }
-    __syncthreads();
+    block_sync<LO>();
     if (part == 0 && e < len) {
         const int rank = below + (int)counters[e];
         if (rank == r_lo) sel[0] = v;
@@ -163,7 +173,7 @@ __device__ inline void rank_directly(const double *list, int len, int below, int
     }
 }
 
-template <int THREADS>
+template <int THREADS, bool LO = false>
 __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi)
 {
     static_assert(THREADS % 64 == 0 && THREADS >= 256 && THREADS <= 1024, "one bucket per thread, at most 16 waves");
@@ -191,7 +201,7 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
                 sh.mm[3 - slot] = 0ull;
             }
             minmax_to_lds(fmin(act0 ? e0 : inf, act1 ? e1 : inf), fmax(act0 ? e0 : 0.0, act1 ? e1 : 0.0), &sh.mm[slot]);
-            __syncthreads();
+            block_sync<LO>();
         }
         const double a = key_f64(sh.mm[slot]), b = key_f64(sh.mm[slot + 1]);
         if (!(a < b)) { // all active values equal (or nothing rankable): both ranks are a
@@ -210,12 +220,12 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
         const int k0 = act0 ? bucket(e0) : 0, k1 = act1 ? bucket(e1) : 0;
         if (act0) atomicAdd(&sh.hist[k0], 1u);
         if (act1) atomicAdd(&sh.hist[k1], 1u);
-        __syncthreads();
+        block_sync<LO>();
         // inclusive prefix sum of the bucket counts: DPP inside the wave, wave totals through LDS
         const unsigned mine = sh.hist[tid];
         unsigned incl = wave_inclusive_scan(mine);
         if (lane == 63) sh.wsum[wave] = incl;
-        __syncthreads();
+        block_sync<LO>();
         unsigned before = 0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) before += (w < wave) ? sh.wsum[w] : 0u;
@@ -229,7 +239,7 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
             sh.misc[4] = mine;
         }
         if (mine > 0 && excl <= q_hi && q_hi < incl) sh.misc[2] = (unsigned)tid;
-        __syncthreads();
+        block_sync<LO>();
         const unsigned b_lo = sh.misc[1], b_hi = sh.misc[2];
         if (b_lo == 0xFFFFFFFFu || b_hi == 0xFFFFFFFFu) break; // unrankable input
         if (b_lo != b_hi) {
@@ -241,7 +251,7 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
             if (act0 && (unsigned)k0 == b_hi) mn = fmin(mn, e0);
             if (act1 && (unsigned)k1 == b_hi) mn = fmin(mn, e1);
             minmax_to_lds(mn, mx, &sh.mm[2 - slot]);
-            __syncthreads();
+            block_sync<LO>();
             if (tid == 0) {
                 sh.sel[0] = key_f64(sh.mm[3 - slot]);
                 sh.sel[1] = key_f64(sh.mm[2 - slot]);
@@ -255,10 +265,10 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
         if (cnt <= kSelDirect) { // gather the bucket into a list and rank it
             if (act0) sh.list[atomicAdd(&sh.misc[0], 1u)] = e0;
             if (act1) sh.list[atomicAdd(&sh.misc[0], 1u)] = e1;
-            rank_directly<THREADS>(sh.list, cnt, below, r_lo, r_hi, sh.sel, sh.counters, false);
+            rank_directly<THREADS, LO>(sh.list, cnt, below, r_lo, r_hi, sh.sel, sh.counters, false);
             return;
         }
-        __syncthreads(); // all reads of misc, hist and wsum are done before the next level clears them
+        block_sync<LO>(); // all reads of misc, hist and wsum are done before the next level clears them
     }
     if (tid == 0) {
         sh.sel[0] = sh.pr[0];
@@ -272,7 +282,7 @@ __device__ inline void select_two_ranks(BwShared &sh, int Pp, int r_lo, int r_hi
 // the caller); on return the writes to it still need a barrier.  write_global = false: st and coef
 // (device memory) are left alone - for workgroups that repeat the computation of another one.
 // Returns h (in every thread).
-template <int THREADS>
+template <int THREADS, bool LO = false>
 __device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, double h_fixed,
                                            DevState *__restrict__ st, float *__restrict__ coef,
                                            float *coef_lds, bool write_global = true)
@@ -290,7 +300,7 @@ __device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, doub
         if (tid < 16) sh.misc[tid] = (tid == 0) ? 0u : 0xFFFFFFFFu;
         if (tid < 4) sh.mm[tid] = (tid & 1) ? 0ull : ~0ull;
     }
-    __syncthreads();
+    block_sync<LO>();
 
     // d2 per pair: direct sums, or S_ii + S_jj - 2 S_ij (clamped at 0) from the centred Gram.
     // Thread p takes pair p: row i is the largest one whose first pair index, i (2n - i - 1) / 2,
@@ -315,7 +325,7 @@ __device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, doub
         dmax = fmax(dmax, d);
     }
     if (buckets) minmax_to_lds(dmin, dmax, &sh.mm[0]); // the range of all values, for the first level
-    __syncthreads();
+    block_sync<LO>();
 
     // Median of the multiset of all n*n entries of d2: n diagonal zeros plus every pair value
     // twice.  Sorted position t of the full list is 0 for t < n and the ((t-n)/2)-th smallest
@@ -325,10 +335,10 @@ __device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, doub
     if (select) {
         // n = 2: position t_lo is one of the diagonal zeros - the other rank is selected twice
         const int r_lo = (t_lo >= n) ? (t_lo - n) / 2 : (t_hi - n) / 2, r_hi = (t_hi - n) / 2;
-        if (buckets) select_two_ranks<THREADS>(sh, Pp, r_lo, r_hi);
-        else rank_directly<THREADS>(sh.pr, Pp, 0, r_lo, r_hi, sh.sel, sh.counters, true);
+        if (buckets) select_two_ranks<THREADS, LO>(sh, Pp, r_lo, r_hi);
+        else rank_directly<THREADS, LO>(sh.pr, Pp, 0, r_lo, r_hi, sh.sel, sh.counters, true);
     }
-    __syncthreads();
+    block_sync<LO>();
     if (tid == 0) { // one thread derives h (a logarithm and two divisions in fp64), LDS hands it on
         const double med = 0.5 * ((t_lo >= n ? sh.sel[0] : 0.0) + sh.sel[1]);
         double hh = (h_fixed > 0.0) ? h_fixed : med / log((double)n + 1.0);
@@ -342,14 +352,14 @@ __device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, doub
             st->n = n;
         }
     }
-    __syncthreads();
+    block_sync<LO>();
     const double h = sh.h;
     const double c2h = (n == 1) ? 0.0 : 2.0 / h;
     const double inv_n = 1.0 / (double)n;
     const double neg_inv_h = -1.0 / h;
 
     for (int e = tid; e < Pp; e += THREADS) sh.S[e] = exp(sh.pr[e] * neg_inv_h); // K per pair, reusing S
-    __syncthreads();
+    block_sync<LO>();
     // K, C, row sums: wave -> row, lane -> column.  K_ij and K_ji are the same LDS entry, so K is
     // exactly symmetric; the diagonal is exactly 1.
     for (int i = tid >> 6; i < n; i += THREADS / 64) {
@@ -379,10 +389,17 @@ __device__ inline double bandwidth_from_sums(BwShared &sh, int n, int mode, doub
 // with write_global also records them in st and coef for svgd_get_last.  Returns h.  THREADS
 // threads, n <= 32 (n(n-1)/2 <= 2 * THREADS).  A workgroup costs what the bandwidth kernel costs, but
 // all of them run at once and the launch, with its gap, is gone.
-template <int THREADS>
+// after_sums() is called once the list has been read and before the arithmetic that needs no
+// memory: the place for the caller to send off loads of its own (issued earlier they would only
+// make the list wait behind them - a wave's loads complete in order).
+struct NoCall {
+    __device__ void operator()() const {}
+};
+template <int THREADS, class AfterSums = NoCall>
 __device__ inline double kernel_matrix_prologue(BwShared &sh, const float *__restrict__ partials, int nparts, int n,
                                                 int mode, double h_fixed, DevState *__restrict__ st,
-                                                float *__restrict__ coef, float *coef_lds, bool write_global)
+                                                float *__restrict__ coef, float *coef_lds, bool write_global,
+                                                AfterSums after_sums = AfterSums{})
 {
     const int P = n * (n + 1) / 2;
     constexpr int U = 16; // loads in flight per thread
@@ -425,8 +442,9 @@ __device__ inline double kernel_matrix_prologue(BwShared &sh, const float *__res
             sh.S[pp] = s;
         }
     }
-    const double h = bandwidth_from_sums<THREADS>(sh, n, mode, h_fixed, st, coef, coef_lds, write_global);
-    __syncthreads();
+    after_sums();
+    const double h = bandwidth_from_sums<THREADS, true>(sh, n, mode, h_fixed, st, coef, coef_lds, write_global);
+    block_sync<true>();
     return h;
 }
 

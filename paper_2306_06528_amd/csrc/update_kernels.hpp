@@ -70,18 +70,6 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
     // is to hide behind when D is small.
     __shared__ __attribute__((aligned(16))) float C[N * N + N];
     float *rho = C + N * N;
-    float c2h;
-    if constexpr (FUSED) {
-        __shared__ BwShared sh;
-        const double h = kernel_matrix_prologue<256>(sh, fa.partials_in, fa.nparts_in, N, kDiff ? kModeDiff : kModeGram,
-                                                     fa.h_fixed, st, coef, C, blockIdx.x == 0);
-        c2h = (N == 1) ? 0.f : (float)(2.0 / h);
-    } else {
-        c2h = st->two_over_h;
-        for (int e = threadIdx.x; e < N * N; e += 256) C[e] = coef[kOffC + e];
-        if (threadIdx.x < N) rho[threadIdx.x] = coef[kOffRho + threadIdx.x];
-        __syncthreads();
-    }
     const int64_t ngroups = (D + 3) >> 2;
     const int64_t nthreads = (int64_t)gridDim.x * 256;
     // PREFETCH (carried pair sums of 9 to 12 particles, where the registers allow a single wave per
@@ -105,13 +93,42 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
     const int64_t cnt = (grp0 < ngroups) ? (ngroups - 1 - grp0) / nthreads + 1 : 0;
     const int64_t gstep = fa.reverse ? -nthreads : nthreads;
     int64_t grp = fa.reverse ? grp0 + (cnt - 1) * nthreads : grp0;
+    // Fused step: the first column group's loads go out in the middle of the prologue, after the
+    // list of partial sums has been read, so that they are in flight during the arithmetic on h and K.
+    // (only a group that lies wholly inside the row: the masked loads of a ragged last group come
+    // with branches and waits of their own and are left to the loop)
+    const bool early = FUSED && cnt > 0 && ((grp << 2) + 4 <= D);
+    float c2h;
+    if constexpr (FUSED) {
+        __shared__ BwShared sh;
+        auto first_loads = [&]() __attribute__((always_inline)) {
+            if (early) {
+                const int64_t c = grp << 2;
+#pragma unroll
+                for (int j = 0; j < N; ++j) {
+                    x[j] = *reinterpret_cast<const f32x4u *>(X + (int64_t)j * ld + c);
+                    z[j] = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(G + (int64_t)j * ld + c));
+                }
+            }
+        };
+        const double h = kernel_matrix_prologue<256>(sh, fa.partials_in, fa.nparts_in, N, kDiff ? kModeDiff : kModeGram,
+                                                     fa.h_fixed, st, coef, C, blockIdx.x == 0, first_loads);
+        c2h = (N == 1) ? 0.f : (float)(2.0 / h);
+    } else {
+        c2h = st->two_over_h;
+        for (int e = threadIdx.x; e < N * N; e += 256) C[e] = coef[kOffC + e];
+        if (threadIdx.x < N) rho[threadIdx.x] = coef[kOffRho + threadIdx.x];
+        __syncthreads();
+    }
     if constexpr (PREFETCH) {
-        if (cnt > 0) load_group(grp);
+        if (cnt > 0 && !early) load_group(grp);
     }
     for (int64_t k = 0; k < cnt; ++k, grp += gstep) {
         const int64_t col = grp << 2;
         const bool full = (col + 4 <= D);
-        if constexpr (!PREFETCH) load_group(grp);
+        if constexpr (!PREFETCH) {
+            if (k > 0 || !early) load_group(grp);
+        }
 
         f32x4 m = f32x4{0.f, 0.f, 0.f, 0.f};
         if constexpr (CARRY && !kDiff) { // centre by the pre-update column mean
