@@ -25,21 +25,21 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
     # (config, carried Gram?, rows padded to 32 floats?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True, True): (2801909.3, 2795580.1),
-    (5, False, True): (2801517.0, 2793492.0),
-    (5, True, False): (4076628.3, 2797113.2),   # mean of the two walking directions (separate instances)
-    (5, False, False): (4069780.0, 2795026.0),
-    (3, True, True): (253541.4, 250530.1),      # D = 2,000,000 is a multiple of 32: ld = D either way
-    (3, False, True): (253570.7, 250000.0),
-    (3, True, False): (253543.7, 250530.1),
-    (3, False, False): (253574.3, 250000.0),
-    (4, True, True): (353621.1, 350786.2),
-    (4, False, True): (360158.2, 352872.1),
-    (4, True, False): (369295.2, 356996.8),
-    (4, False, False): (365577.7, 355082.3),
+    (5, True, True): (2801895.9, 2795580.1),
+    (5, False, True): (2801518.4, 2793492.0),
+    (5, True, False): (4078007.4, 2797113.0),   # mean of the two walking directions (separate instances)
+    (5, False, False): (4071814.4, 2795026.2),
+    (3, True, True): (253547.0, 250530.1),      # D = 2,000,000 is a multiple of 32: ld = D either way
+    (3, False, True): (253573.0, 250000.0),
+    (3, True, False): (253547.6, 250530.1),
+    (3, False, False): (253563.2, 250000.0),
+    (4, True, True): (353107.1, 350761.2),
+    (4, False, True): (360081.2, 352891.0),
+    (4, True, False): (366706.1, 356625.6),
+    (4, False, False): (365473.3, 354843.7),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "99ec18134bdb370311845c64aca271e6b8a44293952aa5440c13fe68ec32e9a6"
+TRAFFIC_SOURCE_SHA256 = "0778e2ab84b85a49644f21abf55df464e2cbabbd78f411aa28a88fb577ed6336"
 
 
 def kernel_source_hash():
