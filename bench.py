@@ -39,7 +39,7 @@ TRAFFIC_COUNTERS = {
     (4, False, False): (365473.3, 354843.7),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "0778e2ab84b85a49644f21abf55df464e2cbabbd78f411aa28a88fb577ed6336"
+TRAFFIC_SOURCE_SHA256 = "7953f07b4df267fdae584eb0e4f1ddf160c17d153cbfd7c91fc4d552af5e6da4"
 
 
 def kernel_source_hash():

@@ -470,7 +470,7 @@ __global__ __launch_bounds__(kBwThreads) void bandwidth_kernel(const double *__r
         // entry pp: consecutive threads read consecutive floats, 16 loads in flight each; the KL
         // sums of an entry meet in LDS (sh.pr is not in use yet).
         const int KL = kBwThreads / P < 32 ? kBwThreads / P : 32; // capped: the KL sums are added serially
-        const int kk = tid / P, pp = tid - kk * P;
+        const int kk = tid / P; // (pp = tid - kk * P)
         double s = 0.0;
         if (kk < KL) {
             constexpr int U = 16;
