@@ -39,7 +39,7 @@ TRAFFIC_COUNTERS = {
     (4, False, False): (365473.3, 354843.7),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "7953f07b4df267fdae584eb0e4f1ddf160c17d153cbfd7c91fc4d552af5e6da4"
+TRAFFIC_SOURCE_SHA256 = "991b09e50aed4673f1aa89f895a018e0b04c79ed0ca36247132cb3caf59fcda0"
 
 
 def kernel_source_hash():

@@ -40,6 +40,7 @@ struct RowTable {
     int64_t x[kMaxN];
     int64_t g[kMaxN];
     int32_t ri[kMaxN]; // (address of X row i / 4) mod 32
+    int32_t aligned;   // host side: every row of X and of G starts on a 128-byte boundary
 };
 // The table travels as a kernel argument (by value: nothing to allocate, copy or keep alive);
 // kernels compiled with ROWS = false take this stand-in instead and never read it.
@@ -47,6 +48,7 @@ struct NoRows {
     int64_t x[1];
     int64_t g[1];
     int32_t ri[1];
+    int32_t aligned;
 };
 template <bool ROWS> struct RowArg { typedef NoRows type; };
 template <> struct RowArg<true> { typedef RowTable type; };

@@ -173,7 +173,6 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
 #pragma unroll
     for (int p = 0; p < NPAIR; ++p) acc[p] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    static_assert(!(ROWS && ORDER != 0), "separate rows: plain order");
     constexpr bool ORDERED = ORDER != 0, STREAM = ORDER == 2;
     const int64_t nfull = D >> 6;
     const uint32_t uper = go.per, uhot = go.hot, ucold = uper - uhot, unfull = (uint32_t)nfull;

@@ -240,7 +240,8 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
     int nparts, mode;
     const float *partials = c->partials; // where the list of partials for pass 2 starts
     // streaming loads in pass 1: X well beyond what the memory-side cache could keep for the update
-    const bool big_x = !rt && (int64_t)n * ld * (int64_t)sizeof(float) > 2 * kMemorySideCacheBytes;
+    const bool big_x = (int64_t)n * ld * (int64_t)sizeof(float) > 2 * kMemorySideCacheBytes;
+    const bool x_aligned = rt ? rt->aligned != 0 : rows_aligned(X, ld);
     if (use_carry) {
         nparts = c->carry_nparts;
         partials += c->carry_off;
@@ -262,7 +263,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
         nparts = clampi((D + 255) / 256, 1, mini(c->num_cu * 2, cap_parts));
         // the ranges of the update that follows (tile_range) and how many of each range's first
         // tiles three quarters of the memory-side cache can hold
-        const bool aligned_next = G_next && !rt && rows_aligned(X, ld) && rows_aligned(G_next, ld);
+        const bool aligned_next = G_next && x_aligned && (rt || rows_aligned(G_next, ld));
         const bool shared_ranges = aligned_next && adjacent_tiles(n, ld);
         int64_t nranges = (int64_t)update_workers(c, n, D, ld, carry_next) * (shared_ranges ? 1 : 4);
         int64_t per = (nfull + nranges - 1) / nranges > 0 ? (nfull + nranges - 1) / nranges : 1;
@@ -274,7 +275,7 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
             per = nfull > 0 ? nfull : 1;
             hot = 0;
         }
-        const bool stream_x = big_x && rows_aligned(X, ld); // slabs of unaligned rows share lines
+        const bool stream_x = big_x && x_aligned; // slabs of unaligned rows share lines
         const uint32_t stride = 4u * (uint32_t)nparts, cold = (uint32_t)(per - hot);
         GramOrder go{(uint32_t)nranges, (uint32_t)per, (uint32_t)hot, 0, 0, 0, 0};
         if (cold) { go.q_cold = stride / cold; go.r_cold = stride % cold; }
@@ -282,7 +283,9 @@ int run_kernel_matrix(svgd_ctx *c, const float *X, int n, int64_t D, int64_t ld,
         // (the order is only worth its bookkeeping for an X well beyond the memory-side cache)
 #define GRAM(NBV)                                                                                            \
     do {                                                                                                     \
-        if (rt) gram_mfma_kernel<NBV, true, 0><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, *rt, go); \
+        if (rt && stream_x) gram_mfma_kernel<NBV, true, 2><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, *rt, go); \
+        else if (rt && big_x) gram_mfma_kernel<NBV, true, 1><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, *rt, go); \
+        else if (rt) gram_mfma_kernel<NBV, true, 0><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, *rt, go); \
         else if (stream_x) gram_mfma_kernel<NBV, false, 2><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}, go); \
         else if (big_x) gram_mfma_kernel<NBV, false, 1><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}, go); \
         else gram_mfma_kernel<NBV, false, 0><<<nparts, 64 * kGramWaves, 0, s>>>(X, n, D, ld, c->partials, NoRows{}, go); \
@@ -353,10 +356,12 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         }
         // rows that all start on a 128-byte boundary (X's and G's) need no re-aligned stores and
         // can be read with streaming loads
-        const bool aligned = !EMIT && !rt && rows_aligned(X, ld) && rows_aligned(G, ld);
+        const bool aligned = !EMIT && (rt ? rt->aligned != 0 : rows_aligned(X, ld) && rows_aligned(G, ld));
 #define UPD(NBV, FULL)                                                                                       \
     do {                                                                                                     \
-        if (!EMIT && !CARRY && rt)                                                                           \
+        if (!EMIT && !CARRY && rt && aligned)                                                                \
+            update_mfma_kernel<NBV, false, FULL, false, true, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, *rt, ua); \
+        else if (!EMIT && !CARRY && rt)                                                                      \
             update_mfma_kernel<NBV, false, FULL, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, *rt, ua); \
         else if (!EMIT && aligned)                                                                           \
             update_mfma_kernel<NBV, false, FULL, CARRY, true, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, ua); \
@@ -740,6 +745,9 @@ int svgd_step_rows(svgd_handle_t c, float *const *X_rows, const float *const *G_
         if (spans[i].lo < spans[i - 1].hi) return SVGD_ERR_INVALID_ARG;
     // row starts relative to row 0 (float pointers are 4-byte aligned, so the differences are whole floats)
     RowTable rt;
+    rt.aligned = 1;
+    for (int i = 0; i < n; ++i)
+        if (((uintptr_t)X_rows[i] | (uintptr_t)G_rows[i]) & 127u) rt.aligned = 0;
     for (int i = 0; i < kMaxN; ++i) {
         const int k = i < n ? i : 0;
         rt.x[i] = (int64_t)(((intptr_t)X_rows[k] - (intptr_t)X_rows[0]) / (intptr_t)sizeof(float));

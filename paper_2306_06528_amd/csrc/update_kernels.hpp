@@ -304,7 +304,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
 {
     static_assert(!FUSED || (CARRY && !ROWS && NB <= 2), "the fused step: carried pair sums, n <= 32");
     static_assert(!(CARRY && EMIT), "the Gram is carried only when X is updated");
-    static_assert(!(ROWS && (EMIT || CARRY || ALIGNED)), "separate rows: plain in-place step, re-aligned stores");
+    static_assert(!(ROWS && (EMIT || CARRY)), "separate rows: plain in-place step");
     static_assert(!REV || (CARRY && !ALIGNED && !FUSED), "the mirrored walk exists for re-aligned stores with carried sums");
     constexpr int NS = 4 * NB; // contraction steps = rows per lane
     constexpr int NPAIR = NB * (NB + 1) / 2;
@@ -614,7 +614,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 }
                 if constexpr (ALIGNED) { // the lane's 16 bytes lie where it loaded x from: whole lines per quarter-wave
                     if (FULLROWS || 16 * bi + 4 * q + r < n)
-                        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(OUT + in_lane + base + (int64_t)(16 * bi + r) * ld));
+                        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(OUT + in_lane + base + (ROWS ? xro[ROWS ? s : 0] : (int64_t)(16 * bi + r) * ld)));
                 }
                 if constexpr (!ALIGNED || CARRY) // staged for the re-aligned stores and/or as Gram operands
                     *reinterpret_cast<f32x4 *>(&cur[cur_index(4 * q + r, 4 * c16)]) = o;

@@ -20,15 +20,17 @@ def svgd():
     return mod
 
 
-def _separate_rows(M, seed):
+def _separate_rows(M, seed, aligned=False):
     """Each row of M copied into an allocation of its own, at a different offset from the
-    allocation's start (so every row has its own alignment), in shuffled allocation order."""
+    allocation's start (so every row has its own alignment; aligned: offsets of whole 128-byte
+    lines, so every row starts on a line boundary), in shuffled allocation order."""
     n, D = M.shape
     rng = np.random.default_rng(seed)
     bufs, rows = [], [None] * n
     for i in rng.permutation(n):
-        off = int(rng.integers(0, 37))
+        off = 32 * int(rng.integers(0, 2)) if aligned else int(rng.integers(0, 37))
         b = torch.full((D + 64,), float("nan"), device=M.device)
+        assert b.data_ptr() % 128 == 0
         b[off:off + D] = M[i]
         bufs.append(b)
         rows[i] = b[off:off + D]
@@ -37,14 +39,15 @@ def _separate_rows(M, seed):
 
 @pytest.mark.parametrize("n,D", [(1, 1000), (2, 65), (3, 50_003), (8, 70_001), (12, 8577), (13, 4099), (16, 8577),
                                  (17, 20_011), (32, 20_001), (33, 5003), (48, 129), (64, 70_001), (64, 63), (5, 300)])
-def test_separate_rows_match_oracle_and_packed_step(svgd, n, D):
+@pytest.mark.parametrize("aligned", [False, True])
+def test_separate_rows_match_oracle_and_packed_step(svgd, n, D, aligned):
     g = torch.Generator(device="cuda")
     g.manual_seed(100 * n + D)
     X0 = torch.randn(n, D, generator=g, device="cuda") * 0.3
     G0 = torch.randn(n, D, generator=g, device="cuda")
     eps = 0.05
-    xb, xr = _separate_rows(X0, 1)
-    gb, gr = _separate_rows(G0, 2)
+    xb, xr = _separate_rows(X0, 1, aligned)
+    gb, gr = _separate_rows(G0, 2, aligned)
     Xp = X0.clone()
     with svgd.Svgd(n, D) as eng:
         eng.step_rows(xr, gr, eps)
@@ -66,6 +69,29 @@ def test_separate_rows_match_oracle_and_packed_step(svgd, n, D):
         off = r.storage_offset()
         assert torch.isnan(b[:off]).all() and torch.isnan(b[off + D:]).all()
     assert torch.equal(torch.stack(gr), G0)
+
+
+@pytest.mark.parametrize("aligned", [False, True])
+@pytest.mark.parametrize("n,D", [(32, 4_400_003), (17, 5_000_003)])
+def test_large_separate_rows(svgd, n, D, aligned):
+    """X beyond twice (n = 32) or 1.25 times (n = 17) the memory-side cache as separate rows: the
+    sizes at which the pairwise pass reorders and streams its loads and the update shares ranges or
+    runs two workgroups per CU.  Against the oracle (h, K, X_new)."""
+    g = torch.Generator(device="cuda")
+    g.manual_seed(n + D)
+    X0 = torch.randn(n, D, generator=g, device="cuda") * 0.05
+    G0 = torch.randn(n, D, generator=g, device="cuda") * 1e-2
+    eps = 1e-3
+    _, xr = _separate_rows(X0, 3, aligned)
+    _, gr = _separate_rows(G0, 4, aligned)
+    with svgd.Svgd(n, D) as eng:
+        eng.step_rows(xr, gr, eps)
+        h, K = eng.get_last(n)
+        torch.cuda.synchronize()
+    ref = orc.step(X0.cpu().numpy(), G0.cpu().numpy(), eps)
+    assert abs(h - ref["h"]) / ref["h"] <= TOL_H
+    assert np.abs(K - ref["K"]).max() <= TOL_K
+    assert_x_new(torch.stack(xr).cpu().numpy(), ref, eps, f"rows n={n} D={D}")
 
 
 def test_rows_of_one_matrix_are_separate_rows_too(svgd):
