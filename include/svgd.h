@@ -149,9 +149,10 @@ int svgd_phi_ld(svgd_handle_t h, const float *X, const float *G, int n, int64_t 
  * its D scores (fp32, 4-byte aligned, any spacing or order; the 2n vectors must not overlap).
  * The arrays are read during the call and need not outlive it.  Plain step: bandwidth from the
  * median (or svgd_set_bandwidth), pair sums recomputed from X; carried sums are neither used nor
- * left behind.  Same results as svgd_step on the packed matrix, at somewhat lower speed (every
- * row has its own alignment, so stores are re-aligned per row and nothing is streamed past the
- * caches).  INVALID_ARG: null or misaligned row pointer, overlapping rows; otherwise as svgd_step.
+ * left behind.  Same results as svgd_step on the packed matrix.  Fastest when all 2n vectors
+ * start on 128-byte boundaries (what separately allocated buffers do): then results are stored
+ * directly and G is streamed past the caches, as for a matrix with padded rows; otherwise every
+ * row has its own alignment, stores are re-aligned per row and nothing streams.  INVALID_ARG: null or misaligned row pointer, overlapping rows; otherwise as svgd_step.
  * Does not synchronise or allocate.
  */
 int svgd_step_rows(svgd_handle_t h, float *const *X_rows, const float *const *G_rows, int n, int64_t D,
