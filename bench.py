@@ -25,18 +25,18 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
     # (config, carried Gram?, rows padded to 32 floats?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True, True): (2801895.9, 2795580.1),
-    (5, False, True): (2801518.4, 2793492.0),
-    (5, True, False): (4078007.4, 2797113.0),   # mean of the two walking directions (separate instances)
-    (5, False, False): (4071814.4, 2795026.2),
-    (3, True, True): (253547.0, 250530.1),      # D = 2,000,000 is a multiple of 32: ld = D either way
-    (3, False, True): (253573.0, 250000.0),
-    (3, True, False): (253547.6, 250530.1),
-    (3, False, False): (253563.2, 250000.0),
-    (4, True, True): (353107.1, 350761.2),
-    (4, False, True): (360081.2, 352891.0),
-    (4, True, False): (366706.1, 356625.6),
-    (4, False, False): (365473.3, 354843.7),
+    (5, True, True): (2801910.6, 2795580.1),
+    (5, False, True): (2801520.9, 2793492.0),
+    (5, True, False): (4075616.8, 2797113.5),   # mean of the two walking directions (separate instances)
+    (5, False, False): (4070070.5, 2795026.2),
+    (3, True, True): (253544.3, 250530.1),      # D = 2,000,000 is a multiple of 32: ld = D either way
+    (3, False, True): (253567.3, 250000.0),
+    (3, True, False): (253540.6, 250530.1),
+    (3, False, False): (253571.7, 250000.0),
+    (4, True, True): (353129.6, 350749.2),
+    (4, False, True): (360054.8, 352865.9),
+    (4, True, False): (366786.8, 356773.7),
+    (4, False, False): (365333.0, 355010.7),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
 TRAFFIC_SOURCE_SHA256 = "991b09e50aed4673f1aa89f895a018e0b04c79ed0ca36247132cb3caf59fcda0"
