@@ -45,12 +45,15 @@ enum svgd_status {
     SVGD_OK = 0,
     SVGD_ERR_INVALID_ARG = -1, /* null pointer, n < 1, D < 1, ld < D, non-finite eps, X aliases G/PHI */
     SVGD_ERR_BAD_HANDLE = -2,  /* null handle or handle already destroyed */
-    SVGD_ERR_TOO_LARGE = -3,   /* n > max_n, D > max_D, or max_n beyond SVGD_MAX_PARTICLES */
+    SVGD_ERR_TOO_LARGE = -3,   /* n > max_n, D > max_D, or max_n / max_D beyond SVGD_MAX_PARTICLES / SVGD_MAX_D */
     SVGD_ERR_ALLOC = -4,       /* device or host allocation failed */
     SVGD_ERR_DEVICE = -5       /* a HIP call failed; see svgd_last_device_error */
 };
 
 #define SVGD_MAX_PARTICLES 64
+/* Longest particle a handle accepts: 2^36 parameters (256 GiB per particle, more than the part holds;
+ * the kernels count 64-column tiles in 32 bits). */
+#define SVGD_MAX_D ((int64_t)1 << 36)
 
 /*
  * svgd_create flag.  The kernel matrix of step t+1 depends only on X after step t (paper App. B.2,
@@ -78,7 +81,7 @@ enum svgd_status {
 #define SVGD_FLAG_FUSE_MFMA 2u
 
 /*
- * Create a handle for problems up to max_n particles (1..SVGD_MAX_PARTICLES) of up to max_D
+ * Create a handle for problems up to max_n particles (1..SVGD_MAX_PARTICLES) of up to max_D (<= SVGD_MAX_D)
  * parameters each on HIP device `device_id` (-1 = the current device); the sizes play the part of
  * the paper's `num_particles` and of the flattened parameter count of its networks (App. B.2, the
  * arguments of the top-level SVGD inference call; its `lengthscale` is svgd_set_bandwidth, its

@@ -565,7 +565,7 @@ int svgd_create(svgd_handle_t *out, int max_n, int64_t max_D, int device_id, uin
     *out = nullptr;
     if (max_n < 1 || max_D < 1 || (flags & ~(uint32_t)(SVGD_FLAG_CARRY_GRAM | SVGD_FLAG_FUSE_MFMA)) != 0 || device_id < -1)
         return SVGD_ERR_INVALID_ARG;
-    if (max_n > SVGD_MAX_PARTICLES) return SVGD_ERR_TOO_LARGE;
+    if (max_n > SVGD_MAX_PARTICLES || max_D > SVGD_MAX_D) return SVGD_ERR_TOO_LARGE;
 
     svgd_ctx *c = new (std::nothrow) svgd_ctx();
     if (!c) return SVGD_ERR_ALLOC;

@@ -54,6 +54,7 @@ def test_create_rejects_bad_arguments(lib):
     assert lib.svgd_create(ctypes.byref(h), 4, 100, 0, 4) == -1      # unknown flag bit
     assert lib.svgd_create(ctypes.byref(h), 4, 100, -2, 0) == -1
     assert lib.svgd_create(ctypes.byref(h), 65, 100, 0, 0) == -3     # beyond SVGD_MAX_PARTICLES
+    assert lib.svgd_create(ctypes.byref(h), 4, (1 << 36) + 1, 0, 0) == -3     # beyond SVGD_MAX_D
     assert not h.value
 
 
