@@ -73,6 +73,7 @@ FLAG_FUSE_MFMA = 2
 KERNEL_KINDS = ("gram", "reduce", "bandwidth", "update")
 MAX_PARTICLES = 64
 STATIC_MAX_D = 1 << 32
+MAX_D = 1 << 36
 
 
 class SvgdError(RuntimeError):
