@@ -39,7 +39,7 @@ TRAFFIC_COUNTERS = {
     (4, False, False): (365333.0, 355010.7),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "991b09e50aed4673f1aa89f895a018e0b04c79ed0ca36247132cb3caf59fcda0"
+TRAFFIC_SOURCE_SHA256 = "6f25cb8a7ff361d8f95e9aa5e4dd0b35098d5e068e1b1dd424f48edae91e70e3"
 
 
 def kernel_source_hash():

@@ -80,6 +80,20 @@ __device__ inline f32x4 load4_stream(const float *__restrict__ row, int64_t col,
     return load4(row, col, D, false);
 }
 
+// Sum of v over the four lanes l, l ^ 16, l ^ 32, l ^ 48 (the four 16-lane rows of a wave), in every
+// lane, as (v[l] + v[l ^ 16]) + (the same of l ^ 32): the gfx950 row-swap instructions exchange
+// whole rows between two registers in the vector ALU, where a shuffle would go through LDS and
+// make the wave wait for it twice.
+__device__ inline float sum_over_rows(float v)
+{
+    const unsigned u = __float_as_uint(v);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false); // rows 1 <-> 0 and 3 <-> 2 of the two copies
+    const float s = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+    const unsigned w = __float_as_uint(s);
+    const auto b = __builtin_amdgcn_permlane32_swap(w, w, false, false); // rows 2, 3 <-> 0, 1
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 // How the matrix-core passes share the nfull = D / 64 full 64-column tiles among nwg worker
 // workgroups of four waves: either every wave owns a contiguous range [t0, t1) (stride 1), or the
 // workgroup owns one and its waves take every fourth tile of it, t0, t0 + 4, ... < t1 (adjacent).

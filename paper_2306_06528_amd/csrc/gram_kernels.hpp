@@ -247,10 +247,7 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
         for (int i = 1; i < RPL; ++i) s += x[i];
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            float v = s[c];
-            v += __shfl_xor(v, 16, kWave);
-            v += __shfl_xor(v, 32, kWave);
-            s[c] = v * inv_n;
+            s[c] = sum_over_rows(s[c]) * inv_n;
         }
         // The LDS region is private to this wave and a wave's LDS operations execute in order, so
         // no barrier is needed between consuming the previous slab and writing this one.

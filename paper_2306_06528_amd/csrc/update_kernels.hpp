@@ -512,10 +512,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             for (int s = 1; s < NS; ++s) m += x[s];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                float v = m[e];
-                v += __shfl_xor(v, 16, kWave);
-                v += __shfl_xor(v, 32, kWave);
-                m[e] = v * inv_n;
+                m[e] = sum_over_rows(m[e]) * inv_n;
             }
             // through the (currently idle) staging block: lane (q, c) knows columns 4c..4c+3,
             // the Gram layout wants columns 4(4st + q)..+3
