@@ -25,18 +25,18 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
     # (config, carried Gram?, rows padded to 32 floats?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True, True): (2801910.6, 2795580.1),
-    (5, False, True): (2801520.9, 2793492.0),
-    (5, True, False): (4075616.8, 2797113.5),   # mean of the two walking directions (separate instances)
-    (5, False, False): (4070070.5, 2795026.2),
-    (3, True, True): (253544.3, 250530.1),      # D = 2,000,000 is a multiple of 32: ld = D either way
-    (3, False, True): (253567.3, 250000.0),
-    (3, True, False): (253540.6, 250530.1),
-    (3, False, False): (253571.7, 250000.0),
-    (4, True, True): (353129.6, 350749.2),
-    (4, False, True): (360054.8, 352865.9),
-    (4, True, False): (366786.8, 356773.7),
-    (4, False, False): (365333.0, 355010.7),
+    (5, True, True): (2801901.7, 2795580.1),
+    (5, False, True): (2801516.2, 2793492.0),
+    (5, True, False): (4078851.4, 2797113.6),   # mean of the two walking directions (separate instances)
+    (5, False, False): (4071866.5, 2795026.0),
+    (3, True, True): (253545.0, 250530.2),      # D = 2,000,000 is a multiple of 32: ld = D either way
+    (3, False, True): (253571.1, 250000.0),
+    (3, True, False): (253548.2, 250530.2),
+    (3, False, False): (253572.8, 250000.0),
+    (4, True, True): (353123.5, 350770.4),
+    (4, False, True): (360072.3, 353216.9),
+    (4, True, False): (366691.8, 356783.9),
+    (4, False, False): (365358.4, 355037.3),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
 TRAFFIC_SOURCE_SHA256 = "6f25cb8a7ff361d8f95e9aa5e4dd0b35098d5e068e1b1dd424f48edae91e70e3"
