@@ -25,21 +25,21 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 # the kernel source: if the hash below no longer matches, "traffic" is reported as null.
 TRAFFIC_COUNTERS = {
     # (config, carried Gram?, rows padded to 32 floats?) -> (FETCH_SIZE KiB, WRITE_SIZE KiB)
-    (5, True, True): (2801901.7, 2795580.1),
-    (5, False, True): (2801516.2, 2793492.0),
-    (5, True, False): (4078851.4, 2797113.6),   # mean of the two walking directions (separate instances)
-    (5, False, False): (4071866.5, 2795026.0),
-    (3, True, True): (253545.0, 250530.2),      # D = 2,000,000 is a multiple of 32: ld = D either way
-    (3, False, True): (253571.1, 250000.0),
-    (3, True, False): (253548.2, 250530.2),
-    (3, False, False): (253572.8, 250000.0),
-    (4, True, True): (353123.5, 350770.4),
-    (4, False, True): (360072.3, 353216.9),
-    (4, True, False): (366691.8, 356783.9),
-    (4, False, False): (365358.4, 355037.3),
+    (5, True, True): (2801879.6, 2795580.1),
+    (5, False, True): (2801515.4, 2793492.0),
+    (5, True, False): (4072296.5, 2797113.5),   # mean of the two walking directions (separate instances)
+    (5, False, False): (4066961.6, 2795026.6),
+    (3, True, True): (253521.8, 250530.1),      # D = 2,000,000 is a multiple of 32: ld = D either way
+    (3, False, True): (253579.1, 250000.0),
+    (3, True, False): (253532.1, 250530.1),
+    (3, False, False): (253573.5, 250000.0),
+    (4, True, True): (353133.5, 350745.0),
+    (4, False, True): (359983.7, 352893.9),
+    (4, True, False): (366806.0, 356675.6),
+    (4, False, False): (365467.2, 354787.4),
 }
 TRAFFIC_SCALE = (2.0, 1.0)     # FETCH_SIZE counts half of the bytes a plain copy reads, WRITE_SIZE all
-TRAFFIC_SOURCE_SHA256 = "6f25cb8a7ff361d8f95e9aa5e4dd0b35098d5e068e1b1dd424f48edae91e70e3"
+TRAFFIC_SOURCE_SHA256 = "4a8b61cedc15aec6e84aa11f16da428b8a6b241d90624b332ae90d20edc9ee1c"
 
 
 def kernel_source_hash():
@@ -148,6 +148,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20,
                     help="untimed steps first (the chip needs some 30 ms of work to reach its steady clocks)")
     ap.add_argument("--config", type=int, default=5, help="workload 1..5 (default 5: n=64, D=11,173,962)")
+    ap.add_argument("--particles", type=int, default=None,
+                    help="another particle count n with the config's distributions (a side measurement, "
+                         "e.g. n = 33; the line then names the size it ran)")
+    ap.add_argument("--params", type=int, default=None, help="another flattened size D, likewise")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--separate-gram", action="store_true",
                     help="run the pairwise-d2 pass as its own kernel every step instead of carrying "
@@ -177,7 +181,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
-    wl = workloads.make(args.config, device="cuda:0")
+    wl = workloads.make(args.config, device="cuda:0", n=args.particles, D=args.params)
     n, D, eps = wl.n, wl.D, wl.cfg.eps
     stream = torch.cuda.current_stream()
 
@@ -316,7 +320,8 @@ def main():
     tiny = n <= 8 and n * D <= 16384   # sizes the library runs as a single kernel
     traffic = None
     key = (args.config, carry, padded)
-    if key in TRAFFIC_COUNTERS and kernel_source_hash() == TRAFFIC_SOURCE_SHA256:
+    resized = args.particles is not None or args.params is not None
+    if not resized and key in TRAFFIC_COUNTERS and kernel_source_hash() == TRAFFIC_SOURCE_SHA256:
         f_kib, w_kib = TRAFFIC_COUNTERS[key]
         traffic = (f_kib * TRAFFIC_SCALE[0] + w_kib * TRAFFIC_SCALE[1]) * 1024.0
 
@@ -333,7 +338,8 @@ def main():
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": f"{wl.cfg.name}: n={n} particles x D={D} fp32, rows {ld} floats apart, eps={eps}",
+        "config": {"workload": f"{wl.cfg.name}{' (resized)' if resized else ''}: n={n} particles x D={D} fp32, "
+                               f"rows {ld} floats apart, eps={eps}",
                    "n": n, "D": D, "ld": ld, "config_index": args.config,
                    "gram": "carried from the previous update" if carry else "separate pass",
                    "fuse_mfma": bool(args.fuse)},

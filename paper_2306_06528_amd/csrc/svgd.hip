@@ -205,24 +205,29 @@ bool beyond_cache(int n, int64_t ld)
     return (int64_t)n * ld * (int64_t)sizeof(float) > kMemorySideCacheBytes + kMemorySideCacheBytes / 4;
 }
 
+// Particle counts one to four above a multiple of 16: the matrix-core update treats the extra
+// particles as remainder rows (template argument REM of update_mfma_kernel).
+bool has_remainder_rows(int n) { return n > 16 && (n & 15) >= 1 && (n & 15) <= 4; }
+
 // Whether the matrix-core update on aligned rows lets the waves of a workgroup share a range.
 bool adjacent_tiles(int n, int64_t ld) { return n > 48 || beyond_cache(n, ld); }
 
 // Worker workgroups of the matrix-core update (each walks ranges of 64-column tiles; one more
 // workgroup does D mod 64): one per CU - the kernel overlaps its own loads with its multiplies, and
-// fewer concurrent row streams keep more HBM pages open.  Exception: particle counts just above
-// 16, whose tiles cost the instructions of 32 rows but move little more than half the bytes, so
-// that the fixed costs of a tile show.  The kernel instances for n not a multiple of 16, n < 32,
-// are built for two waves per SIMD, and for 17 <= n <= 24 and an X beyond the memory-side cache
-// two workgroups per CU overlap one's arithmetic with the other's loads (with carried sums at
-// D = 5,000,000: n = 17 225 -> 190 us, n = 24 258 -> 241 us; from n = 25 on the gain is below the
-// cost of the longer list of partial sums, with 16 or 32 particles the second workgroup costs
-// 2-5 %, and for an X that cache serves it costs 9 %).
+// fewer concurrent row streams keep more HBM pages open.  Exception: 21 to 24 particles, whose
+// tiles cost the instructions of 32 rows but move little more than half the bytes, so that the
+// fixed costs of a tile show (17 to 20 are 16 rows plus remainder rows, see has_remainder_rows).
+// The kernel instances for n not a multiple of 16, n < 32, are built for two waves per SIMD, and
+// for those particle counts and an X beyond the memory-side cache two workgroups per CU overlap
+// one's arithmetic with the other's loads (with carried sums at D = 5,000,000: n = 24
+// 258 -> 241 us; from n = 25 on the gain is below the cost of the longer list of partial sums,
+// with 16 or 32 particles the second workgroup costs 2-5 %, and for an X that cache serves it
+// costs 9 %).
 // The Gram pass splits the tiles the same way.
 int update_workers(const svgd_ctx *c, int n, int64_t D, int64_t ld, bool carry)
 {
     const int64_t nfull = D / 64;
-    const int per_cu = (n >= 17 && n <= 24 && beyond_cache(n, ld)) ? 2 : 1;
+    const int per_cu = (n >= 17 && n <= 24 && !has_remainder_rows(n) && beyond_cache(n, ld)) ? 2 : 1;
     const int max_workers = mini(c->num_cu * per_cu, (carry ? max_parts(c, n) : kMaxParts) - 1);
     return clampi((nfull + 3) / 4, 1, max_workers);
 }
@@ -370,7 +375,26 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         else                                                                                                 \
             update_mfma_kernel<NBV, EMIT, FULL, CARRY, false, false><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, ua); \
     } while (0)
-        if (n == 16) UPD(1, true);
+        // one to four particles beyond a multiple of 16 ride along as remainder rows of the kernel
+        // for that multiple
+#define UPD_REM(NBV)                                                                                         \
+    do {                                                                                                     \
+        if (!EMIT && !CARRY && rt && aligned)                                                                \
+            update_mfma_kernel<NBV, false, true, false, true, true, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, *rt, ua); \
+        else if (!EMIT && !CARRY && rt)                                                                      \
+            update_mfma_kernel<NBV, false, true, false, false, true, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, *rt, ua); \
+        else if (!EMIT && aligned)                                                                           \
+            update_mfma_kernel<NBV, false, true, CARRY, true, false, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, ua); \
+        else if (CARRY && ua.reverse)                                                                        \
+            update_mfma_kernel<NBV, false, true, CARRY, false, false, false, CARRY, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, ua); \
+        else                                                                                                 \
+            update_mfma_kernel<NBV, EMIT, true, CARRY, false, false, false, false, true><<<grid, 256, 0, s>>>(X, G, PHI, c->coef, c->state, n, D, ld, eps, c->partials, NoRows{}, ua); \
+    } while (0)
+        const bool rem = has_remainder_rows(n);
+        if (rem && n < 32) UPD_REM(1);
+        else if (rem && n < 48) UPD_REM(2);
+        else if (rem) UPD_REM(3);
+        else if (n == 16) UPD(1, true);
         else if (NB == 1) UPD(1, false);
         else if (n == 32) UPD(2, true);
         else if (n == 48) UPD(3, true);
@@ -378,6 +402,7 @@ int run_update(svgd_ctx *c, float *X, const float *G, float *PHI, int n, int64_t
         else if (NB == 2) UPD(2, false);
         else if (NB == 3) UPD(3, false);
         else UPD(4, false);
+#undef UPD_REM
 #undef UPD
     }
     hipError_t e = hipGetLastError();
@@ -437,7 +462,13 @@ int run_update_fused(svgd_ctx *c, float *X, const float *G, int n, int64_t D, in
         else                                                                                                 \
             update_mfma_kernel<NBV, false, FULL, true, false, false, true><<<grid, 256, 0, s>>>(X, G, nullptr, c->coef, c->state, n, D, ld, eps, gram_out, NoRows{}, fa); \
     } while (0)
-        if (n == 16) UPD(1, true);
+        if (has_remainder_rows(n)) { // 17..20
+            if (aligned)
+                update_mfma_kernel<1, false, true, true, true, false, true, false, true><<<grid, 256, 0, s>>>(X, G, nullptr, c->coef, c->state, n, D, ld, eps, gram_out, NoRows{}, fa);
+            else
+                update_mfma_kernel<1, false, true, true, false, false, true, false, true><<<grid, 256, 0, s>>>(X, G, nullptr, c->coef, c->state, n, D, ld, eps, gram_out, NoRows{}, fa);
+        }
+        else if (n == 16) UPD(1, true);
         else if (n < 16) UPD(1, false);
         else if (n == 32) UPD(2, true);
         else UPD(2, false);

@@ -218,7 +218,8 @@ __global__ __launch_bounds__(256) void update_valu_kernel(float *__restrict__ X,
 // Columns beyond the last full tile (D mod 64) are done by one extra workgroup with a plain
 // loop.  Rows >= n (n not a multiple of 16) are neither loaded nor stored; their A entries are
 // zero (their contraction steps still run: skipping them behind wave-uniform branches cost more
-// than it saved, see below).
+// than it saved, see below).  One to four rows beyond a multiple of 16 do not get a block of
+// their own at all (REM, below).
 // ---------------------------------------------------------------------------------------------
 constexpr int kUpdCur = 16 * 64;    // floats per wave
 constexpr int kUpdCarry = 64 * 32;  // floats per wave
@@ -293,8 +294,16 @@ __device__ inline void opaque(int64_t &v) { asm volatile("" : "+v"(v)); }
 // has to mask its left edge, is a separate, branchy instance of the same code.
 // ROWS: the particles are n separately allocated rows; row addresses (and store alignments) come
 // from a RowTable instead of i * ld (plain in-place step only, re-aligned stores).
+// REM: n = 16 NB + R with 1 <= R <= 4.  A whole further block of 16 rows for those few particles
+// would cost a tile the instructions of 16 more rows while it moves the bytes of R; instead the R
+// remainder rows ride along in one register per array - lane (q, c) holds row 16 NB + q, columns
+// 4c..4c+3, exactly one contraction step of the matrix instruction.  Their contribution to the
+// other rows' phi is that one extra step per output block; their own phi, R x n x 64 products,
+// is summed on the vector ALU (each lane over its own rows, then across the wave's four rows of
+// lanes); they are stored as one more store group, and their pair sums (CARRY) are accumulated
+// like those of a further block whose rows R..15 are zero.
 template <int NB, bool EMIT, bool FULLROWS, bool CARRY, bool ALIGNED = false, bool ROWS = false, bool FUSED = false,
-          bool REV = false>
+          bool REV = false, bool REM = false>
 __global__ __launch_bounds__(256)
 __attribute__((amdgpu_waves_per_eu((NB <= 2 && !FULLROWS) ? 2 : 1, (NB <= 2 && !FULLROWS) ? 2 : 1)))
 void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, float *__restrict__ PHI,
@@ -306,8 +315,11 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     static_assert(!(CARRY && EMIT), "the Gram is carried only when X is updated");
     static_assert(!(ROWS && (EMIT || CARRY)), "separate rows: plain in-place step");
     static_assert(!REV || (CARRY && !ALIGNED && !FUSED), "the mirrored walk exists for re-aligned stores with carried sums");
+    static_assert(!REM || (FULLROWS && NB <= 3), "remainder rows come after full blocks");
     constexpr int NS = 4 * NB; // contraction steps = rows per lane
-    constexpr int NPAIR = NB * (NB + 1) / 2;
+    constexpr int NBG = NB + (REM ? 1 : 0); // blocks as the pair sums see them
+    constexpr int NPAIR = NBG * (NBG + 1) / 2;
+    const int R = REM ? n - 16 * NB : 0; // remainder rows
     // [A operands: NB*NB*64 float4][4 waves x (cur + carry)]
     __shared__ __attribute__((aligned(16))) float lds[NB * NB * 64 * 4 + 4 * (kUpdCur + kUpdCarry)];
     const int lane = threadIdx.x & 63;
@@ -377,6 +389,30 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         const int row = 16 * (s >> 2) + 4 * q + (s & 3);
         rho[s] = (FULLROWS || row < n) ? rhov[row] : 0.f;
     }
+    // remainder rows.  arem: the A operand of their one contraction step for output block bi -
+    // lane (q, m) holds C[16bi + m][16NB + q].  crem: for remainder row r and lane row q the
+    // coefficients C[16NB + r][.] of the rows that a lane of that q holds, in the order of its
+    // registers (NS rows of the full blocks, then row 16NB + q), padded to a multiple of four.
+    constexpr int CREM = NS + 4;
+    __shared__ float arem[REM ? NB * 64 : 1];
+    __shared__ __attribute__((aligned(16))) float crem[REM ? 16 * CREM : 4];
+    float rho_r = 0.f;
+    if constexpr (REM) {
+        for (int e = threadIdx.x; e < NB * 64; e += 256) {
+            const int l = e & 63, bi = e >> 6;
+            arem[e] = ((l >> 4) < R) ? Cm[(16 * bi + (l & 15)) * n + 16 * NB + (l >> 4)] : 0.f;
+        }
+        for (int e = threadIdx.x; e < 16 * CREM; e += 256) {
+            const int s = e % CREM, rq = e / CREM, r = rq >> 2, qq = rq & 3;
+            float v = 0.f;
+            if (r < R) {
+                if (s < NS) v = Cm[(16 * NB + r) * n + 16 * (s >> 2) + 4 * qq + (s & 3)];
+                else if (s == NS && qq < R) v = Cm[(16 * NB + r) * n + 16 * NB + qq];
+            }
+            crem[e] = v;
+        }
+        if (q < R) rho_r = rhov[16 * NB + q];
+    }
     __syncthreads();
 
     // The tiles of this wave: t0, t0 + TS, ... < t1.  Re-aligned stores hand a row's tail from one
@@ -437,6 +473,15 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     constexpr bool XBUF = (NB <= 2);
     constexpr bool GBUF = (NB <= 2) || CARRY;
     f32x4 x[NS], z[NS], xn[XBUF ? NS : 1], gn[GBUF ? NS : 1];
+    // remainder rows: this tile's x and z, and the next tile's x and g (always fetched a tile ahead)
+    f32x4 xr = {0.f, 0.f, 0.f, 0.f}, zr = xr, xrn = xr, grn = xr;
+    int64_t rem_x, rem_g; // row 16NB + q relative to in_lane (which has 4q ld on one array)
+    if constexpr (ROWS) {
+        rem_x = (REM && q < R) ? rt.x[ROWS ? 16 * NB + q : 0] : 0;
+        rem_g = (REM && q < R) ? rt.g[ROWS ? 16 * NB + q : 0] : 0;
+    } else {
+        rem_x = rem_g = (int64_t)(16 * NB - 3 * q) * ld;
+    }
     // G is read exactly once per step.  When no cache line is shared between tiles or rows
     // (ALIGNED) it is loaded with the streaming hint, which does not allocate on the way in:
     // measurably faster (a plain read-read-write stream over these buffers runs at 5.25 instead of
@@ -459,6 +504,14 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         const int urow = 16 * (s >> 2) + (s & 3);
         if (FULLROWS || urow + 4 * q < n) z[s] = load16g(gt + (ROWS ? gro[ROWS ? s : 0] : (int64_t)urow * ld));
     };
+    auto load_next_rem = [&](const float *xt, const float *gt) __attribute__((always_inline)) {
+        if constexpr (REM) {
+            if (q < R) {
+                xrn = load16x(xt + rem_x);
+                grn = load16g(gt + rem_g);
+            }
+        }
+    };
     auto load_next = [&](const float *xt, const float *gt) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
@@ -468,6 +521,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 if constexpr (GBUF) gn[s] = load16g(gt + (ROWS ? gro[ROWS ? s : 0] : (int64_t)urow * ld));
             }
         }
+        load_next_rem(xt, gt);
     };
     if (t0 < t1) {
         int64_t in_off = in_lane + (t_first << 6);
@@ -501,15 +555,24 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 if constexpr (XBUF) x[s] = xn[s];
                 if constexpr (GBUF) z[s] = gn[s];
             }
+            if constexpr (REM) {
+                xr = xrn;
+                zr = grn;
+            }
             load_next(xt, gt);
+        } else if constexpr (REM) {
+            xr = xrn;
+            zr = grn;
+            load_next_rem(xt, gt);
         }
 
         f32x4 mg[CARRY ? 4 : 1];      // pre-update column means in the Gram operand layout
-        f32x4 ag[CARRY ? NB : 1][4];  // Gram operands of the blocks finished so far
+        f32x4 ag[CARRY ? NBG : 1][4]; // Gram operands of the blocks finished so far
         if constexpr (CARRY) {
             f32x4 m = x[0];
 #pragma unroll
             for (int s = 1; s < NS; ++s) m += x[s];
+            if constexpr (REM) m += xr; // zero in the lanes without a remainder row
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 m[e] = sum_over_rows(m[e]) * inv_n;
@@ -522,6 +585,24 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         }
 #pragma unroll
         for (int s = 0; s < NS; ++s) z[s] -= c2h * x[s];
+        // phi of the remainder rows: lane (q, c) ends up with that of row 16NB + q
+        f32x4 phir = {0.f, 0.f, 0.f, 0.f};
+        if constexpr (REM) {
+            zr -= c2h * xr;
+            for (int r = 0; r < R; ++r) { // wave-uniform trip count
+                const float *cr = crem + (4 * r + q) * CREM;
+                f32x4 p = cr[NS] * zr;
+#pragma unroll
+                for (int sg = 0; sg < NB; ++sg) {
+                    const f32x4 c4 = *reinterpret_cast<const f32x4 *>(cr + 4 * sg);
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) p += c4[k] * z[4 * sg + k];
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) p[e] = sum_over_rows(p[e]);
+                if (q == r) phir = p;
+            }
+        }
 
         // E(b), one of its four store groups: 4 rows x 256 B, lane (rl = q, p = c16)
         auto emit_group = [&](int b, int k) __attribute__((always_inline)) {
@@ -540,7 +621,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
                 if constexpr (REV) v[e] = cur[(o >= 64) ? (kUpdCur + row * 32 + o - 64) : cur_index(rloc, o)];
                 else v[e] = cur[(o < 0) ? (kUpdCur + row * 32 + 32 + o) : cur_index(rloc, o)];
             }
-            if (FULLROWS || row < n) {
+            if ((FULLROWS && !(REM && b == NB)) || row < n) {
                 float *dst = ot + (ROWS ? srow[ROWS ? row : 0] : (int64_t)urow * ld) + sh;
                 if constexpr (!FIRST) {
                     __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(dst));
@@ -562,7 +643,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         };
         // G(b), the part that pairs block b with block b0 <= b
         auto gram_pair = [&](int b0, int b) __attribute__((always_inline)) {
-            const int pidx = b0 * NB - (b0 * (b0 - 1)) / 2 + (b - b0);
+            const int pidx = b0 * NBG - (b0 * (b0 - 1)) / 2 + (b - b0);
 #pragma unroll
             for (int st4 = 0; st4 < 4; ++st4)
 #pragma unroll
@@ -584,6 +665,11 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
                         acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(a4[k], z[4 * sg + k][t], acc[t], 0, 0, 0);
+                if (REM && sg == NB - 1) { // the remainder rows' contraction step
+                    const float ar = arem[bi * 64 + lane];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) acc[t] = __builtin_amdgcn_mfma_f32_16x16x4f32(ar, zr[t], acc[t], 0, 0, 0);
+                }
                 if (!GBUF && bi == NB - 1) { // z rows 4sg..4sg+3 are dead: fetch the next tile's g
 #pragma unroll
                     for (int k = 0; k < 4; ++k) load_g(gt, 4 * sg + k);
@@ -638,6 +724,32 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
             }
         }
         if constexpr (!ALIGNED) carry_copy(NB - 1);
+        if constexpr (REM) {
+            // the remainder rows: epilogue, staging as rows 0..3 of a further block, one store group
+            f32x4 o;
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float phi = fmaf(rho_r, xr[t], phir[t]);
+                o[t] = EMIT ? phi : fmaf(eps, phi, xr[t]);
+            }
+            if constexpr (ALIGNED) {
+                if (q < R) __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(OUT + in_lane + base + rem_x));
+            }
+            if constexpr (!ALIGNED || CARRY) *reinterpret_cast<f32x4 *>(&cur[cur_index(q, 4 * c16)]) = o;
+            if constexpr (CARRY) {
+#pragma unroll
+                for (int st4 = 0; st4 < 4; ++st4) {
+                    const f32x4 v = *reinterpret_cast<const f32x4 *>(&cur[cur_index(c16 & 3, 4 * (4 * st4 + q))]) - mg[st4];
+                    ag[NB][st4] = (c16 < R) ? v : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+            }
+            if constexpr (!ALIGNED) emit_group(NB, 0);
+            if constexpr (CARRY) {
+#pragma unroll
+                for (int b0 = 0; b0 <= NB; ++b0) gram_pair(b0, NB);
+            }
+            if constexpr (!ALIGNED) carry_copy(NB);
+        }
     };
 
     if constexpr (ALIGNED) { // no left edge to mask
@@ -652,7 +764,7 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
     // flush: the last r_i columns of the range (REV: its first 32 - r_i) are still in the carry
     if (!ALIGNED && t1 > t0) {
         const int64_t c_end = t1 << 6;
-        for (int idx = lane; idx < 16 * NB * 32; idx += 64) {
+        for (int idx = lane; idx < 16 * NBG * 32; idx += 64) {
             const int row = idx >> 5, cc = idx & 31;
             const int ri = ROWS ? sri[ROWS ? row : 0] : (int)((a0 + (uint32_t)row * dm) & 31u);
             if constexpr (REV) {
@@ -680,9 +792,9 @@ void update_mfma_kernel(float *__restrict__ X, const float *__restrict__ G, floa
         float *out = gram_out + (int64_t)blockIdx.x * P;
         int p = 0;
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
+        for (int b = 0; b < NBG; ++b) {
 #pragma unroll
-            for (int b2 = b; b2 < NB; ++b2) {
+            for (int b2 = b; b2 < NBG; ++b2) {
                 if ((p & 3) == wave) {
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {

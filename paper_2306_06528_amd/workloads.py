@@ -94,15 +94,24 @@ def _uniforms_torch(bits: torch.Tensor):
     return (hi + 0.5) * (1.0 / 4294967296.0), (lo + 0.5) * (1.0 / 4294967296.0)
 
 
+# elements per batch of tensor operations: on the CPU what the caches like; on a GPU large, so that
+# a big workload takes hundreds of kernel launches, not tens of thousands (a profiler that
+# collects hardware counters instruments every launch)
 _CHUNK = 1 << 22
+_CHUNK_GPU = 1 << 27
+
+
+def _chunk(device) -> int:
+    return _CHUNK if torch.device(device).type == "cpu" else _CHUNK_GPU
 
 
 def uniform(seed: int, array_id: int, numel: int, device="cpu") -> torch.Tensor:
     """numel uniforms in (0, 1), fp32 (the upper 32 bits of each hash)."""
     base = stream_base(seed, array_id)
     out = torch.empty(numel, dtype=torch.float32, device=device)
-    for s0 in range(0, numel, _CHUNK):
-        c = min(_CHUNK, numel - s0)
+    step = _chunk(device)
+    for s0 in range(0, numel, step):
+        c = min(step, numel - s0)
         u1, _ = _uniforms_torch(_bits_torch(base, s0, c, device))
         out[s0:s0 + c] = u1.to(torch.float32)
     return out
@@ -112,8 +121,9 @@ def normal(seed: int, array_id: int, numel: int, device="cpu") -> torch.Tensor:
     """numel standard normal variates, fp32: sqrt(-2 ln u1) cos(2 pi u2) per element."""
     base = stream_base(seed, array_id)
     out = torch.empty(numel, dtype=torch.float32, device=device)
-    for s0 in range(0, numel, _CHUNK):
-        c = min(_CHUNK, numel - s0)
+    step = _chunk(device)
+    for s0 in range(0, numel, step):
+        c = min(step, numel - s0)
         u1, u2 = _uniforms_torch(_bits_torch(base, s0, c, device))
         out[s0:s0 + c] = (torch.sqrt(-2.0 * torch.log(u1)) * torch.cos((2.0 * np.pi) * u2)).to(torch.float32)
     return out

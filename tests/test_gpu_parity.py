@@ -493,6 +493,20 @@ def test_carried_gram_matches_oracle_every_step(svgd, n, D, padded):
     check_carried_chain(svgd, X, G, 0.05, padded=padded, steps=4)
 
 
+@pytest.mark.parametrize("padded", [False, True])
+@pytest.mark.parametrize("D", [197, 300_007])
+@pytest.mark.parametrize("n", [17, 18, 19, 20, 33, 34, 35, 36, 49, 50, 51, 52])
+def test_particle_counts_just_above_a_multiple_of_16(svgd, n, D, padded):
+    """One to four particles beyond a multiple of 16 are carried through the matrix-core update
+    as remainder rows of the kernel for that multiple: a plain step (h, K, phi on all columns,
+    in-place update to one ulp) and four carried steps (both walking directions, the remainder
+    rows' pair sums feeding the next step's h and K), at a D with a few tiles in all and one that
+    gives every wave several."""
+    X, G = _random_problem(n, D, 7 * n + D, x_std=0.3)
+    _plain_step_check(svgd, X, G, 0.05, padded=padded)
+    check_carried_chain(svgd, X, G, 0.05, padded=padded, steps=4)
+
+
 @pytest.mark.parametrize("n,D", [(16, 8577), (13, 4099), (24, 20_011), (32, 8577), (32, 4096), (17, 1531), (8, 100_003)])
 def test_fused_single_launch_step_on_request(svgd, n, D):
     """SVGD_FLAG_FUSE_MFMA: with a short list of carried sums the step is one launch also on the
