@@ -625,7 +625,7 @@ def test_random_shapes(svgd, seed):
     check_carried_chain(svgd, X0, G, eps, padded=padded, steps=3)
 
 
-@pytest.mark.parametrize("n", [8, 32, 64])
+@pytest.mark.parametrize("n", [8, 20, 32, 33, 64])
 @pytest.mark.parametrize("shift", [1, 3, 17])
 def test_buffers_with_odd_base_alignment(svgd, n, shift):
     """X, G and PHI that start `shift` floats into their allocations (each with a different
