@@ -270,6 +270,32 @@ def main():
                     best = {"gbs": gbs, "ms": ms, "pattern": pattern, "workgroups": cus * per_cu}
         return best
 
+    def read_ceiling(Xv):
+        """What the memory system gives the pairwise pass's traffic and nothing else: every element
+        of X read once (svgd_diag_read_rows), best of the two access shapes, with and without
+        streaming loads, and of four grid sizes.  GB/s at 4 bytes per element."""
+        cus = torch.cuda.get_device_properties(0).multi_processor_count
+        best = None
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        for pattern in range(4):
+            for per_cu in (1, 2, 4, 8):
+                sink = torch.empty(cus * per_cu, device=Xv.device)
+                for _ in range(3):
+                    svgd.diag_read_rows(Xv, sink, pattern, stream=stream)
+                e0.record(stream)
+                for _ in range(reps):
+                    svgd.diag_read_rows(Xv, sink, pattern, stream=stream)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / reps
+                gbs = 4 * n * D / (ms * 1e-3) / 1e9
+                if args.verbose:
+                    print(f"read_rows pattern {pattern} x {per_cu}/CU: {ms:.4f} ms {gbs:.0f} GB/s", file=sys.stderr)
+                if best is None or gbs > best["gbs"]:
+                    best = {"gbs": gbs, "ms": ms, "pattern": pattern, "workgroups": cus * per_cu}
+        return best
+
     carry = not args.separate_gram
     flags = svgd.FLAG_CARRY_GRAM if carry else 0
     if args.fuse:
@@ -293,8 +319,12 @@ def main():
     # (b) with densely packed rows (ld = D), (c) both: the plain svgd_step(X, G, n, D, eps, stream)
     # of the four-call ABI on a handle without flags - 16 bytes per particle-param
     alt = None
+    gram_ms_sep = None
     if carry:
         alt = side(timed(0, X, G), STEP_BYTES_PER_PARAM, gram="separate pass")
+        res = timed(0, X, G, kinds=("gram",))
+        if res[1]["gram"][1] > 0:
+            gram_ms_sep = res[1]["gram"][0] / res[1]["gram"][1]
     alt_dense = alt_plain = None
     if padded:
         _, Xd = laid_out(wl.X0, False)
@@ -316,6 +346,18 @@ def main():
     upd_ms = prof_upd["update"][0] / max(prof_upd["update"][1], 1)   # over the timed steps
     upd_gbs = UPDATE_BYTES_PER_PARAM * n * D / (upd_ms * 1e-3) / 1e9
     gram_gbs = 4 * n * D / (kern_ms["gram"] * 1e-3) / 1e9 if kern_ms["gram"] > 0 else None
+    # the pairwise pass as its own kernel (this run's, or the separate-pass alternative's) against
+    # the peak and against a plain read of the same rows
+    gram_ms = kern_ms["gram"] if kern_ms["gram"] > 0 else gram_ms_sep
+    gram_pass = None
+    if gram_ms:
+        rc = None if args.no_ceiling else read_ceiling(X)
+        g_gbs = 4 * n * D / (gram_ms * 1e-3) / 1e9
+        gram_pass = {"kernel_ms": gram_ms, "gbs": g_gbs, "frac": g_gbs / HBM_PEAK_GBS,
+                     "read_ceiling": rc and rc["gbs"],
+                     "read_ceiling_kernel": rc and (f"svgd_diag_read_rows pattern {rc['pattern']}, "
+                                                    f"{rc['workgroups']} workgroups, {rc['ms']:.4f} ms"),
+                     "frac_of_read_ceiling": rc and g_gbs / rc["gbs"]}
 
     tiny = n <= 8 and n * D <= 16384   # sizes the library runs as a single kernel
     traffic = None
@@ -353,6 +395,7 @@ def main():
         "dense_rows": alt_dense,
         "plain_svgd_step": alt_plain,
         "gram_gbs": gram_gbs,
+        "gram_pass": gram_pass,
         "roofline": {
             "kernel": "step_tiny_kernel (the whole step in one workgroup)" if tiny else
                       ("update_valu_kernel" if n <= 12 else "update_mfma_kernel") +

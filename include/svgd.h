@@ -230,6 +230,21 @@ int svgd_diag_axpy_rows(float *X, const float *G, int n, int64_t D, int64_t ld, 
                         int workgroups, void *stream);
 
 /*
+ * Diagnostic: the memory traffic of the pairwise-distance pass and nothing else - every element of
+ * the n rows of X (DEVICE, D floats each, ld floats apart, 4-byte aligned) is read once, 4 bytes
+ * per element, and added up; workgroup w leaves its sum in sink[w] (DEVICE array of `workgroups`
+ * floats, the caller's).  Timing it on the buffers a benchmark uses gives the rate that this part's
+ * memory system sustains for a pure read of these row streams: the practical ceiling of the pass
+ * that forms the pair sums.  `pattern` 0: a wave instruction covers 4 rows x 256 bytes (the
+ * matrix-core pass's shape), 1: 1 KiB of one row (the vector-ALU pass's shape); 2, 3: the same
+ * with the streaming (no-allocate) hint on the loads.  Other values: SVGD_ERR_INVALID_ARG.
+ * `workgroups` (1..65536) of 256 threads stride over the column tiles.  Enqueued on `stream` of the
+ * current device; does not synchronise or allocate.
+ */
+int svgd_diag_read_rows(const float *X, int n, int64_t D, int64_t ld, float *sink, int pattern, int workgroups,
+                        void *stream);
+
+/*
  * Multi-SWAG running moments (paper Sec. 2: SWAG keeps the first and second moments of a
  * network's parameter trajectory, multi-SWAG for every particle of the ensemble).  Absorbs one
  * more iterate X (DEVICE, n x D fp32, row-major, contiguous) into the running means after `count`

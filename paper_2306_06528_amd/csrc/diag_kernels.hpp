@@ -74,4 +74,51 @@ __global__ __launch_bounds__(256) void diag_axpy_rows_kernel(float *__restrict__
     }
 }
 
+// The traffic shape of the pairwise pass and nothing else: every element of n rows of D floats,
+// ld floats apart, is read once with 16-byte loads and added up (so that the loads cannot be
+// dropped); one float per workgroup goes to sink[blockIdx.x].  PAT and NT as above (NT = 1: the
+// loads carry the streaming hint), eight loads in flight per lane, workgroups stride over the
+// full tiles with their waves on adjacent tiles, the columns after the last full tile are read
+// element-wise by the last workgroup.
+template <int PAT, int NT>
+__global__ __launch_bounds__(256) void diag_read_rows_kernel(const float *__restrict__ X, int n, int64_t D, int64_t ld,
+                                                             float *__restrict__ sink)
+{
+    constexpr int TC = PAT == 0 ? 64 : 256;
+    constexpr int RPI = PAT == 0 ? 4 : 1;
+    constexpr int U = 8;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int q = lane >> 4, c16 = lane & 15;
+    const int64_t nfull = D / TC;
+    const int lrow = PAT == 0 ? q : 0;
+    const int64_t lcol = PAT == 0 ? 4 * c16 : 4 * lane;
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+    for (int64_t tile = (int64_t)blockIdx.x * 4 + wave; tile < nfull; tile += (int64_t)gridDim.x * 4) {
+        const int64_t col = tile * TC + lcol;
+        for (int r0 = 0; r0 < n; r0 += U * RPI) {
+            f32x4 x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int row = r0 + u * RPI + lrow;
+                const int64_t off = (int64_t)(row < n ? row : n - 1) * ld + col;
+                if constexpr (NT == 1) x[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(X + off));
+                else x[u] = *reinterpret_cast<const f32x4u *>(X + off);
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                if (r0 + u * RPI + lrow < n) acc += x[u];
+        }
+    }
+    float t = (acc.x + acc.y) + (acc.z + acc.w);
+    if (blockIdx.x == gridDim.x - 1) {
+        const int64_t c0 = nfull * TC, ntail = D - c0;
+        for (int64_t e = threadIdx.x; e < ntail * n; e += 256) t += X[(e / ntail) * ld + c0 + e % ntail];
+    }
+    __shared__ float part[4];
+    t = wave_sum(t);
+    if (lane == 0) part[wave] = t;
+    __syncthreads();
+    if (threadIdx.x == 0) sink[blockIdx.x] = (part[0] + part[1]) + (part[2] + part[3]);
+}
+
 } // namespace svgd

@@ -894,6 +894,21 @@ int svgd_diag_axpy_rows(float *X, const float *G, int n, int64_t D, int64_t ld, 
     return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
 }
 
+int svgd_diag_read_rows(const float *X, int n, int64_t D, int64_t ld, float *sink, int pattern, int workgroups,
+                        void *stream)
+{
+    if (!X || !sink || n < 1 || D < 1 || ld < D || workgroups < 1 || workgroups > 65536 || pattern < 0 || pattern > 3)
+        return SVGD_ERR_INVALID_ARG;
+    hipStream_t st = (hipStream_t)stream;
+    switch (pattern) {
+    case 0: diag_read_rows_kernel<0, 0><<<workgroups, 256, 0, st>>>(X, n, D, ld, sink); break;
+    case 1: diag_read_rows_kernel<1, 0><<<workgroups, 256, 0, st>>>(X, n, D, ld, sink); break;
+    case 2: diag_read_rows_kernel<0, 1><<<workgroups, 256, 0, st>>>(X, n, D, ld, sink); break;
+    default: diag_read_rows_kernel<1, 1><<<workgroups, 256, 0, st>>>(X, n, D, ld, sink); break;
+    }
+    return hipGetLastError() == hipSuccess ? SVGD_OK : SVGD_ERR_DEVICE;
+}
+
 int swag_update_moments(float *mean, float *sqmean, const float *X, int n, int64_t D, int64_t count,
                         void *stream)
 {

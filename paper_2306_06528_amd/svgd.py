@@ -44,6 +44,9 @@ _lib.svgd_diag_copy.restype = ctypes.c_int
 _lib.svgd_diag_axpy_rows.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                      ctypes.c_float, ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
 _lib.svgd_diag_axpy_rows.restype = ctypes.c_int
+_lib.svgd_diag_read_rows.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p,
+                                     ctypes.c_int, ctypes.c_int, ctypes.c_void_p]
+_lib.svgd_diag_read_rows.restype = ctypes.c_int
 _lib.svgd_step_static.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                   ctypes.c_float, ctypes.c_void_p]
 _lib.svgd_step_static.restype = ctypes.c_int
@@ -139,6 +142,20 @@ def diag_axpy_rows(X: torch.Tensor, G: torch.Tensor, s: float, pattern: int, wor
         raise ValueError("G must have the shape and row stride of X")
     n, D, ld = shape
     rc = _lib.svgd_diag_axpy_rows(X.data_ptr(), G.data_ptr(), n, D, ld, float(s), int(pattern), int(workgroups),
+                                  _stream_ptr(stream))
+    if rc != SVGD_OK:
+        raise SvgdError(rc)
+
+
+def diag_read_rows(X: torch.Tensor, sink: torch.Tensor, pattern: int, stream=None):
+    """Reads every element of the rows of X once (the pairwise pass's memory traffic and nothing
+    else; see svgd_diag_read_rows); sink: float32 CUDA vector, one entry per workgroup, receives the
+    workgroups' sums."""
+    n, D, ld = _rows_of(X, "X")
+    if (not isinstance(sink, torch.Tensor) or sink.dtype is not torch.float32 or not sink.is_cuda
+            or sink.dim() != 1 or not sink.is_contiguous() or sink.numel() < 1):
+        raise TypeError("sink must be a contiguous 1-D float32 CUDA tensor")
+    rc = _lib.svgd_diag_read_rows(X.data_ptr(), n, D, ld, sink.data_ptr(), int(pattern), int(sink.numel()),
                                   _stream_ptr(stream))
     if rc != SVGD_OK:
         raise SvgdError(rc)

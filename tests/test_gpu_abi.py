@@ -88,6 +88,27 @@ def test_profiling_selects_kernel_kinds(mod):
         assert [v[1] for v in eng.profile_end().values()] == [0, 0, 0, 0]
 
 
+@pytest.mark.parametrize("pattern", [0, 1, 2, 3])
+@pytest.mark.parametrize("n,D,ld", [(64, 20_011, 20_032), (8, 70_001, 70_001), (33, 1000, 1003), (3, 63, 64)])
+def test_diag_read_rows(mod, pattern, n, D, ld):
+    """The read yardstick reads every element of the n x D window exactly once: with ones inside the
+    window and large values in the padding, the workgroups' sums add up to n * D exactly (integers
+    that fp32 holds), whatever the grid."""
+    buf = torch.full((n, ld), 1e6, device="cuda")
+    X = buf[:, :D]
+    X.fill_(1.0)
+    for workgroups in (1, 7, 300):
+        sink = torch.full((workgroups,), float("nan"), device="cuda")
+        mod.diag_read_rows(X, sink, pattern)
+        torch.cuda.synchronize()
+        assert float(sink.double().sum().item()) == float(n * D)
+    sink = torch.zeros(4, device="cuda")
+    assert mod._lib.svgd_diag_read_rows(X.data_ptr(), n, D, ld, sink.data_ptr(), 4, 4, None) == -1
+    assert mod._lib.svgd_diag_read_rows(X.data_ptr(), n, D, ld, sink.data_ptr(), 0, 0, None) == -1
+    assert mod._lib.svgd_diag_read_rows(X.data_ptr(), n, D, D - 1, sink.data_ptr(), 0, 4, None) == -1
+    assert mod._lib.svgd_diag_read_rows(None, n, D, ld, sink.data_ptr(), 0, 4, None) == -1
+
+
 @pytest.mark.parametrize("pattern", list(range(12)) + [16, 21, 27])
 @pytest.mark.parametrize("n,D,ld", [(64, 20_011, 20_032), (8, 70_001, 70_001), (33, 1000, 1003), (3, 63, 64)])
 def test_diag_axpy_rows(mod, pattern, n, D, ld):
