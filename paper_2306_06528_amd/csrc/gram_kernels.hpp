@@ -4,6 +4,7 @@
 // Here all pairs are accumulated in ONE pass over X: a thread (or a wave) holds all n values of
 // a few columns on chip, adds their contribution to every pair, and moves on.
 #pragma once
+#include <type_traits>
 #include "common.hpp"
 
 namespace svgd {
@@ -217,7 +218,13 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
 #pragma unroll
         for (int i = 0; i < RPL; ++i) xro[i] = (4 * i + q < n) ? rt.x[ROWS ? 4 * i + q : 0] : 0;
     }
-    auto load_slab = [&]() __attribute__((always_inline)) { // the slab at `at`; then on to the next index
+    // The slab at `at` (then on to the next index): where it lies and how it is to be loaded -
+    // 0: plain 16-byte loads, 1: streaming ones, 2: the partial slab, 3: an empty slab.  One
+    // wave-uniform decision per slab, then sixteen loads in a row: decided per row, every load
+    // sat behind its own little tree of branches, a hundred branches per slab during which the
+    // matrix pipe had nothing from this wave.
+    int64_t col = 0;
+    auto next_slab = [&]() __attribute__((always_inline)) -> int {
         const bool is_cold = ORDERED && phase == 0;
         int64_t tile = ORDERED ? nfull : (int64_t)at; // ordered, phase 2: the partial slab
         if (ORDERED && phase < 2) {
@@ -227,21 +234,36 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
         }
         advance();
         const int64_t wcol = tile << 6;
-        const int64_t col = wcol + 4 * c16;
-        const bool full = (wcol + 64 <= D);
+        col = wcol + 4 * c16;
+        if (ORDERED && tile < 0) return 3;
+        if (wcol + 64 > D) return 2;
+        return (STREAM && is_cold) ? 1 : 0;
+    };
+    auto rows = [&](auto how) __attribute__((always_inline)) {
+        constexpr int HOW = decltype(how)::value;
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int row = 4 * i + q;
-            if ((!ORDERED || tile >= 0) && row < n) {
-                const float *xr = X + (ROWS ? xro[ROWS ? i : 0] : (int64_t)row * ld);
-                x[i] = (STREAM && is_cold) ? load4_stream(xr, col, D, full) : load4(xr, col, D, full);
-            } else {
-                x[i] = f32x4{0.f, 0.f, 0.f, 0.f}; // an empty slab adds nothing to any sum
+            const float *xr = X + (ROWS ? xro[ROWS ? i : 0] : (int64_t)row * ld);
+            f32x4 v = {0.f, 0.f, 0.f, 0.f}; // rows beyond n, and empty slabs, add nothing to any sum
+            if (HOW != 3 && row < n) {
+                if constexpr (HOW == 0) v = *reinterpret_cast<const f32x4u *>(xr + col);
+                else if constexpr (HOW == 1) v = __builtin_nontemporal_load(reinterpret_cast<const f32x4u *>(xr + col));
+                else v = load4(xr, col, D, false);
             }
+            x[i] = v;
         }
     };
-    if (lo < nidx) load_slab();
-    for (uint32_t idx = lo; idx < nidx; idx += stride) {
+    // run `f` with the load mode as a compile-time constant
+    auto with_mode = [&](int how, auto f) __attribute__((always_inline)) {
+        if (how == 0) f(std::integral_constant<int, 0>{});
+        else if (how == 1) f(std::integral_constant<int, 1>{});
+        else if (how == 2) f(std::integral_constant<int, 2>{});
+        else f(std::integral_constant<int, 3>{});
+    };
+    auto load_slab = [&]() __attribute__((always_inline)) { with_mode(next_slab(), rows); };
+    // steps 2 and 3: the slab in x, centred, into `buf`
+    auto centre_and_stage = [&](float *buf) __attribute__((always_inline)) {
         f32x4 s = x[0];
 #pragma unroll
         for (int i = 1; i < RPL; ++i) s += x[i];
@@ -250,22 +272,23 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
             s[c] = sum_over_rows(s[c]) * inv_n;
         }
         // The LDS region is private to this wave and a wave's LDS operations execute in order, so
-        // no barrier is needed between consuming the previous slab and writing this one.
+        // no barrier is needed between consuming a slab and overwriting it.
 #pragma unroll
         for (int i = 0; i < RPL; ++i) {
             const int row = 4 * i + q;
             // rows >= n hold -mean here; they only reach entries with i or j >= n, never stored
-            *reinterpret_cast<f32x4 *>(&my[row * 64 + ((c16 ^ (row & 15)) << 2)]) = x[i] - s;
+            *reinterpret_cast<f32x4 *>(&buf[row * 64 + ((c16 ^ (row & 15)) << 2)]) = x[i] - s;
         }
-        // the next slab's loads are in flight while this one is multiplied
-        if (idx + stride < nidx) load_slab();
+    };
+    // steps 4 and 5 on the slab in `buf`
+    auto multiply = [&](const float *buf) __attribute__((always_inline)) {
 #pragma unroll
         for (int st = 0; st < 4; ++st) {
             f32x4 a[NB];
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int row = 16 * b + c16; // here c16 plays the role of rr (matrix row)
-                a[b] = *reinterpret_cast<const f32x4 *>(&my[row * 64 + (((4 * st + q) ^ c16) << 2)]);
+                a[b] = *reinterpret_cast<const f32x4 *>(&buf[row * 64 + (((4 * st + q) ^ c16) << 2)]);
             }
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -280,6 +303,17 @@ __global__ __launch_bounds__(64 * kGramWaves) void gram_mfma_kernel(const float 
                 }
             }
         }
+    };
+    // Two workgroups per CU, i.e. two waves per SIMD, take turns at the matrix pipe.  (One wave per
+    // SIMD that overlaps the steps itself - two slabs in its LDS region; slab t multiplied while
+    // slab t+1 is centred and staged and the loads of slab t+2 go out, all in one basic block -
+    // was slower: 632 against 566 us at n = 64, D = 11.2 M.)
+    if (lo < nidx) load_slab();
+    for (uint32_t idx = lo; idx < nidx; idx += stride) {
+        centre_and_stage(my);
+        // the next slab's loads are in flight while this one is multiplied
+        if (idx + stride < nidx) load_slab();
+        multiply(my);
     }
 
     // combine the waves through LDS, then store the upper triangle in tri(i, j) order
